@@ -1,0 +1,163 @@
+/*
+ * shplb.h -- C ABI of the S-HPLB hot path on one MI355X (gfx950).
+ *
+ * The path: causal attention prefill in which every head runs under its own
+ * sparsity budget (paper Sections 3.1-3.3).  Three device steps and one host step:
+ *
+ *   shplb_block_scores          pooled query/key block importance logits
+ *   shplb_select_topk_per_head  per-head top-k key-block selection
+ *   shplb_sparse_attn_prefill   block-sparse causal attention over the selection,
+ *                               work items dealt to compute units by descending cost
+ *   shplb_balance_heads         greedy head-to-partition assignment (host)
+ *
+ * Conventions
+ *   - Every function returns an int32 status: 0 = OK, negative = error (see
+ *     SHPLB_E_*).  Nothing throws.  shplb_strerror() gives a text.
+ *   - "device" pointers are HIP device memory owned by the caller; the library
+ *     never allocates, frees or keeps them.  "host" pointers are ordinary memory,
+ *     read (or written) synchronously before the call returns.
+ *   - Device work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and is asynchronous; outputs are bit-identical from run
+ *     to run (each work item owns its output rows; scheduling order never changes
+ *     results).
+ *   - Tensors are token-major: Q is [T, n_q_heads, head_dim] bf16 with element
+ *     strides (q_stride_t, q_stride_h, 1); K and V are [T, n_kv_heads, head_dim]
+ *     bf16 with strides (kv_stride_t, kv_stride_h, 1).  T = cu_seqlens[n_seq].
+ *     Base pointers and strides must keep every head row 16-byte aligned.
+ *   - Sequences are split into blocks of `block` tokens; a block never straddles
+ *     two sequences; the last block of a sequence may be ragged.
+ *     nb_s = ceil(len_s / block).
+ *   - Row index of (sequence s, query head h, query block i):
+ *       row = (sum_{s'<s} nb_s') * n_q_heads + h * nb_s + i.
+ *   - GQA: query head h reads KV head h / (n_q_heads / n_kv_heads) (Section 2.1).
+ */
+#ifndef SHPLB_H
+#define SHPLB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SHPLB_API __attribute__((visibility("default")))
+
+#define SHPLB_OK              0
+#define SHPLB_E_NULL        (-1)  /* a required pointer is NULL */
+#define SHPLB_E_SHAPE       (-2)  /* bad shape, stride, alignment or cu_seqlens */
+#define SHPLB_E_BUDGET      (-3)  /* negative budget, or partition cannot hold the units */
+#define SHPLB_E_WORKSPACE   (-4)  /* reserved: workspace too small */
+#define SHPLB_E_UNSUPPORTED (-5)  /* head_dim != 128, block not 64/128, too many sequences/blocks */
+#define SHPLB_E_HIP         (-6)  /* a HIP call or kernel launch failed */
+
+#define SHPLB_MAX_SEQ        64    /* sequences per call */
+#define SHPLB_MAX_BLOCKS   4096    /* blocks per sequence */
+
+typedef struct {
+  int32_t n_seq;                 /* 1..SHPLB_MAX_SEQ */
+  const int32_t* cu_seqlens;     /* host [n_seq+1]; cu[0] = 0, strictly increasing */
+  int32_t n_q_heads, n_kv_heads; /* n_q_heads % n_kv_heads == 0 */
+  int32_t head_dim;              /* 128 */
+  int32_t block;                 /* 64 or 128 */
+  int64_t q_stride_t, q_stride_h;   /* element strides of Q (and of the output O) */
+  int64_t kv_stride_t, kv_stride_h; /* element strides of K and V */
+  float softmax_scale;           /* > 0, or 0 for 1/sqrt(head_dim) (Eq. 1) */
+} shplb_problem;
+
+/* Per-workgroup record written by shplb_sparse_attn_prefill when asked for. */
+typedef struct {
+  uint32_t xcc_id;        /* accelerator die the workgroup ran on */
+  uint32_t cu_id;         /* (shader engine << 8) | compute unit inside the die */
+  uint32_t n_items;       /* (head, query block) items it processed */
+  uint32_t cost_blocks;   /* selected key blocks over those items */
+  uint64_t t_first;       /* constant-rate device clock at its first item */
+  uint64_t t_last;        /* ... after its last item */
+} shplb_wg_stats;
+
+/* ---- host-side shape helpers (no device work) --------------------------- */
+
+/* Number of (sequence, head, query block) rows. */
+SHPLB_API int32_t shplb_num_rows(const shplb_problem* p, int64_t* rows_out /*host*/);
+
+/* Bytes of device workspace any entry point below needs for this problem. */
+SHPLB_API int32_t shplb_workspace_bytes(const shplb_problem* p, int64_t* bytes_out /*host*/);
+
+/* Layout of the score buffer: sequence s occupies floats
+ * [seq_offsets[s], seq_offsets[s+1]) as a row-major [n_q_heads, nb_s, nb_s]
+ * array; seq_offsets[n_seq] is the total float count. */
+SHPLB_API int32_t shplb_score_layout(const shplb_problem* p, int64_t* seq_offsets_out /*host [n_seq+1]*/);
+
+/* CSR row pointer of the selection, closed form: row (s,h,i) holds
+ * min(clamp(budgets[s*n_q_heads+h], 2, nb_s), i+1) blocks -- the head's budget
+ * (in blocks, applied to every query-block row of the head; Section 3.1), never
+ * fewer than the always-kept sink and diagonal blocks, never more than the
+ * causal-visible blocks. */
+SHPLB_API int32_t shplb_sel_row_ptr(const shplb_problem* p, const int32_t* budgets /*host [n_seq*n_q_heads]*/,
+                          int64_t* sel_ptr_out /*host [rows+1]*/);
+
+/* Workgroups the attention launch uses on the current device (size of the
+ * sched_stats_out array). */
+SHPLB_API int32_t shplb_sched_num_workgroups(const shplb_problem* p, int32_t* n_out /*host*/);
+
+/* ---- device steps -------------------------------------------------------- */
+
+/* Block importance (the estimator the paper leaves to its borrowed kernels,
+ * Section 4; scale from Eq. 1): mean-pool the valid tokens of every query block
+ * and key block, then scores[s][h][i][j] = (Qbar[h,i] . Kbar[h/G,j]) * scale for
+ * j <= i.  Entries with j > i are not written.  fp32 throughout.
+ *   q, k: device bf16.  scores_out: device fp32, shplb_score_layout() floats.
+ *   workspace: device, shplb_workspace_bytes(). */
+SHPLB_API int32_t shplb_block_scores(const shplb_problem* p, const void* q, const void* k,
+                           float* scores_out, void* workspace, void* stream);
+
+/* Per-head top-k selection (Sections 2.3-2.4: a per-head budget applied as a
+ * top-k, which needs only the order of the scores).  Row (s,h,i) keeps block 0
+ * and block i, then the highest-scoring blocks among 1..i-1 until it holds
+ * sel_ptr[row+1]-sel_ptr[row] blocks; equal scores go to the lower block index
+ * (+0 and -0 are equal; NaN scores are a caller error).  Indices are written
+ * ascending.
+ *   scores: device fp32 as written by shplb_block_scores.
+ *   budgets: host [n_seq*n_q_heads], validated (>= 0); sel_ptr: device int64
+ *   [rows+1], the array shplb_sel_row_ptr() fills for the same budgets.
+ *   sel_idx_out: device int32 [sel_ptr[rows]]. */
+SHPLB_API int32_t shplb_select_topk_per_head(const shplb_problem* p, const float* scores,
+                                   const int32_t* budgets, const int64_t* sel_ptr,
+                                   int32_t* sel_idx_out, void* stream);
+
+/* Block-sparse causal attention (Eq. 1 restricted to the selected key blocks,
+ * token-level causal mask inside the diagonal block), bf16 MFMA with fp32
+ * accumulation and fp32 online softmax.  Work items are the rows; they are
+ * ordered by descending selected-block count and handed to persistent
+ * workgroups through one device counter: the greedy rule of Section 3.3 (largest
+ * first, to whichever worker is free first) applied to compute units.
+ *   sel_ptr/sel_idx: device CSR; every row's list must be ascending, within
+ *   [0, i], and contain i (lists written by shplb_select_topk_per_head are).
+ *   out: device bf16 [T, n_q_heads, head_dim], strides as Q.
+ *   lse_out: device fp32 [n_q_heads, T] natural-log softmax denominators, or NULL.
+ *   sched_stats_out: device shplb_wg_stats[shplb_sched_num_workgroups()], or NULL.
+ *   workspace: device, shplb_workspace_bytes(); must not be shared with a call
+ *   still in flight on another stream. */
+SHPLB_API int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* q, const void* k,
+                                  const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
+                                  void* out, float* lse_out, void* sched_stats_out,
+                                  void* workspace, void* stream);
+
+/* ---- host step ------------------------------------------------------------ */
+
+/* Sparsity-aware head-to-partition assignment (Section 3.3, Eq. 2): visit units
+ * by descending cost (equal costs: ascending index), give each to the part with
+ * the smallest load so far (equal loads: lowest part index).
+ * max_per_part = 0 is the paper's algorithm; > 0 additionally caps the number of
+ * units per part (equal-sized GQA shares).  All pointers are host memory.
+ *   costs [n] (>= 0), part_of_out [n], loads_out [n_parts] or NULL.
+ * Errors: SHPLB_E_NULL; SHPLB_E_SHAPE (n < 0, n_parts < 1); SHPLB_E_BUDGET
+ * (negative cost, or max_per_part * n_parts < n). */
+SHPLB_API int32_t shplb_balance_heads(const int64_t* costs, int32_t n, int32_t n_parts,
+                            int32_t max_per_part, int32_t* part_of_out, int64_t* loads_out);
+
+SHPLB_API const char* shplb_strerror(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHPLB_H */

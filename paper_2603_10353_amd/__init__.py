@@ -1,0 +1,24 @@
+"""S-HPLB hot path on one MI355X: head-adaptive block-sparse causal prefill.
+
+Thin ctypes binding over libshplb.so (hand-written HIP for gfx950).  The functions
+carry the names of the C entry points declared in include/shplb.h and only marshal
+arguments; every step of the path runs in the library's kernels.  There is no CPU
+fallback: importing works without the library, calling does not.
+"""
+from .binding import (  # noqa: F401
+    Problem,
+    ShplbError,
+    WgStats,
+    lib_path,
+    load_library,
+    shplb_balance_heads,
+    shplb_block_scores,
+    shplb_num_rows,
+    shplb_sched_num_workgroups,
+    shplb_score_layout,
+    shplb_sel_row_ptr,
+    shplb_select_topk_per_head,
+    shplb_sparse_attn_prefill,
+    shplb_strerror,
+    shplb_workspace_bytes,
+)

@@ -1,0 +1,240 @@
+// C-ABI entry points of libshplb: argument validation, geometry, workspace layout,
+// the host-side greedy partition, and dispatch to the kernel launchers.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "shplb_internal.h"
+
+namespace shplb {
+
+static inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
+
+int32_t make_geometry(const shplb_problem* p, Geometry* g) {
+  if (!p || !p->cu_seqlens) return SHPLB_E_NULL;
+  if (p->n_seq < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1) return SHPLB_E_SHAPE;
+  if (p->n_seq > SHPLB_MAX_SEQ) return SHPLB_E_UNSUPPORTED;
+  if (p->n_q_heads % p->n_kv_heads) return SHPLB_E_SHAPE;
+  if (p->head_dim != kHeadDim) return SHPLB_E_UNSUPPORTED;
+  if (p->block != 64 && p->block != 128) return SHPLB_E_UNSUPPORTED;
+  if (p->cu_seqlens[0] != 0) return SHPLB_E_SHAPE;
+  if (!(p->softmax_scale >= 0.0f) || !std::isfinite(p->softmax_scale)) return SHPLB_E_SHAPE;
+  // head rows must be 16-byte aligned and must not overlap
+  if (p->q_stride_h < kHeadDim || p->kv_stride_h < kHeadDim) return SHPLB_E_SHAPE;
+  if (p->q_stride_t < p->q_stride_h * p->n_q_heads) return SHPLB_E_SHAPE;
+  if (p->kv_stride_t < p->kv_stride_h * p->n_kv_heads) return SHPLB_E_SHAPE;
+  if ((p->q_stride_t | p->q_stride_h | p->kv_stride_t | p->kv_stride_h) & 7) return SHPLB_E_SHAPE;
+
+  std::memset(g, 0, sizeof(*g));
+  SeqMeta& m = g->meta;
+  m.n_seq = p->n_seq;
+  m.n_q_heads = p->n_q_heads;
+  m.n_kv_heads = p->n_kv_heads;
+  m.block = p->block;
+  int64_t score_off = 0;
+  int32_t max_nb = 0;
+  for (int s = 0; s < p->n_seq; ++s) {
+    const int64_t len = int64_t(p->cu_seqlens[s + 1]) - p->cu_seqlens[s];
+    if (len < 1) return SHPLB_E_SHAPE;
+    const int64_t nb = (len + p->block - 1) / p->block;
+    if (nb > SHPLB_MAX_BLOCKS) return SHPLB_E_UNSUPPORTED;
+    m.tok_begin[s] = p->cu_seqlens[s];
+    m.blk_begin[s + 1] = m.blk_begin[s] + int32_t(nb);
+    m.score_off[s] = score_off;
+    score_off += int64_t(p->n_q_heads) * nb * nb;
+    max_nb = std::max<int32_t>(max_nb, int32_t(nb));
+  }
+  m.tok_begin[p->n_seq] = p->cu_seqlens[p->n_seq];
+  m.score_off[p->n_seq] = score_off;
+  g->total_tokens = p->cu_seqlens[p->n_seq];
+  g->total_blocks = m.blk_begin[p->n_seq];
+  g->rows = g->total_blocks * p->n_q_heads;
+  if (g->rows > (int64_t(1) << 30)) return SHPLB_E_UNSUPPORTED;
+  g->max_nb = max_nb;
+  g->st = Strides{p->q_stride_t, p->q_stride_h, p->kv_stride_t, p->kv_stride_h};
+  g->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt(float(kHeadDim));
+  return SHPLB_OK;
+}
+
+WorkspaceLayout make_layout(const Geometry& g) {
+  WorkspaceLayout w;
+  int64_t off = 0;
+  w.qbar = off; off += align256(int64_t(g.meta.n_q_heads) * g.total_blocks * kHeadDim * 4);
+  w.kbar = off; off += align256(int64_t(g.meta.n_kv_heads) * g.total_blocks * kHeadDim * 4);
+  w.order = off; off += align256(g.rows * 4);
+  const int64_t n_chunks = (g.rows + kOrderChunk - 1) / kOrderChunk;
+  w.hist = off; off += align256(n_chunks * kCostBins * 4);
+  w.bin_start = off; off += align256(int64_t(kCostBins) * 4);
+  w.ticket = off; off += 256;
+  w.total = off;
+  return w;
+}
+
+int32_t persistent_workgroups() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return SHPLB_E_HIP;
+  if (dev < 0 || dev >= 64) return SHPLB_E_HIP;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      return SHPLB_E_HIP;
+    cached[dev] = cus * 2;   // two 128-thread workgroups per compute unit (one wave per SIMD)
+  }
+  return cached[dev];
+}
+
+}  // namespace shplb
+
+using namespace shplb;
+
+extern "C" {
+
+int32_t shplb_num_rows(const shplb_problem* p, int64_t* rows_out) {
+  if (!rows_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  *rows_out = g.rows;
+  return SHPLB_OK;
+}
+
+int32_t shplb_workspace_bytes(const shplb_problem* p, int64_t* bytes_out) {
+  if (!bytes_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  *bytes_out = make_layout(g).total;
+  return SHPLB_OK;
+}
+
+int32_t shplb_score_layout(const shplb_problem* p, int64_t* seq_offsets_out) {
+  if (!seq_offsets_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  for (int s = 0; s <= g.meta.n_seq; ++s) seq_offsets_out[s] = g.meta.score_off[s];
+  return SHPLB_OK;
+}
+
+int32_t shplb_sel_row_ptr(const shplb_problem* p, const int32_t* budgets, int64_t* sel_ptr_out) {
+  if (!budgets || !sel_ptr_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  const SeqMeta& m = g.meta;
+  for (int64_t x = 0; x < int64_t(m.n_seq) * m.n_q_heads; ++x)
+    if (budgets[x] < 0) return SHPLB_E_BUDGET;
+  int64_t row = 0, acc = 0;
+  sel_ptr_out[0] = 0;
+  for (int s = 0; s < m.n_seq; ++s) {
+    const int64_t nb = m.blk_begin[s + 1] - m.blk_begin[s];
+    for (int h = 0; h < m.n_q_heads; ++h) {
+      const int64_t keep = std::min<int64_t>(std::max<int64_t>(budgets[s * m.n_q_heads + h], 2), nb);
+      for (int64_t i = 0; i < nb; ++i) {
+        acc += std::min<int64_t>(keep, i + 1);
+        sel_ptr_out[++row] = acc;
+      }
+    }
+  }
+  return SHPLB_OK;
+}
+
+int32_t shplb_sched_num_workgroups(const shplb_problem* p, int32_t* n_out) {
+  if (!n_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  const int32_t n = persistent_workgroups();
+  if (n < 0) return n;
+  *n_out = n;
+  return SHPLB_OK;
+}
+
+int32_t shplb_block_scores(const shplb_problem* p, const void* q, const void* k,
+                           float* scores_out, void* workspace, void* stream) {
+  if (!q || !k || !scores_out || !workspace) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 15) return SHPLB_E_SHAPE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return SHPLB_E_SHAPE;
+  const WorkspaceLayout w = make_layout(g);
+  char* ws = static_cast<char*>(workspace);
+  return launch_pool_scores(g, q, k, scores_out, reinterpret_cast<float*>(ws + w.qbar),
+                            reinterpret_cast<float*>(ws + w.kbar), static_cast<hipStream_t>(stream));
+}
+
+int32_t shplb_select_topk_per_head(const shplb_problem* p, const float* scores,
+                                   const int32_t* budgets, const int64_t* sel_ptr,
+                                   int32_t* sel_idx_out, void* stream) {
+  if (!scores || !budgets || !sel_ptr || !sel_idx_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  for (int64_t x = 0; x < int64_t(g.meta.n_seq) * g.meta.n_q_heads; ++x)
+    if (budgets[x] < 0) return SHPLB_E_BUDGET;
+  return launch_select(g, scores, sel_ptr, sel_idx_out, static_cast<hipStream_t>(stream));
+}
+
+int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* q, const void* k,
+                                  const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
+                                  void* out, float* lse_out, void* sched_stats_out,
+                                  void* workspace, void* stream) {
+  if (!q || !k || !v || !sel_ptr || !sel_idx || !out || !workspace) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
+       reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(out)) & 15)
+    return SHPLB_E_SHAPE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return SHPLB_E_SHAPE;
+  const int32_t n_wg = persistent_workgroups();
+  if (n_wg < 0) return n_wg;
+  const WorkspaceLayout w = make_layout(g);
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (int32_t rc = launch_order(g, sel_ptr, w, ws, st)) return rc;
+  return launch_attention(g, q, k, v, sel_ptr, sel_idx, out, lse_out,
+                          static_cast<shplb_wg_stats*>(sched_stats_out),
+                          reinterpret_cast<const int32_t*>(ws + w.order),
+                          reinterpret_cast<uint32_t*>(ws + w.ticket), n_wg, st);
+}
+
+// Greedy multiway partition of Section 3.3.  n is a head (or KV-group) count, so
+// the O(n * n_parts) scan for the least-loaded part is as good as a heap here.
+int32_t shplb_balance_heads(const int64_t* costs, int32_t n, int32_t n_parts,
+                            int32_t max_per_part, int32_t* part_of_out, int64_t* loads_out) {
+  if (n < 0 || n_parts < 1 || max_per_part < 0) return SHPLB_E_SHAPE;
+  if (n > 0 && (!costs || !part_of_out)) return SHPLB_E_NULL;
+  if (max_per_part > 0 && int64_t(max_per_part) * n_parts < n) return SHPLB_E_BUDGET;
+  for (int32_t x = 0; x < n; ++x)
+    if (costs[x] < 0) return SHPLB_E_BUDGET;
+  std::vector<int32_t> visit(n);
+  std::iota(visit.begin(), visit.end(), 0);
+  std::stable_sort(visit.begin(), visit.end(),
+                   [&](int32_t a, int32_t b) { return costs[a] > costs[b]; });
+  std::vector<int64_t> load(n_parts, 0);
+  std::vector<int32_t> held(n_parts, 0);
+  for (int32_t x : visit) {
+    int32_t to = -1;
+    for (int32_t d = 0; d < n_parts; ++d) {
+      if (max_per_part > 0 && held[d] >= max_per_part) continue;
+      if (to < 0 || load[d] < load[to]) to = d;
+    }
+    part_of_out[x] = to;
+    load[to] += costs[x];
+    held[to] += 1;
+  }
+  if (loads_out) std::copy(load.begin(), load.end(), loads_out);
+  return SHPLB_OK;
+}
+
+const char* shplb_strerror(int32_t status) {
+  switch (status) {
+    case SHPLB_OK: return "ok";
+    case SHPLB_E_NULL: return "required pointer is null";
+    case SHPLB_E_SHAPE: return "bad shape, stride, alignment, scale or cu_seqlens";
+    case SHPLB_E_BUDGET: return "negative budget or cost, or partition cannot hold the units";
+    case SHPLB_E_WORKSPACE: return "workspace too small";
+    case SHPLB_E_UNSUPPORTED: return "unsupported configuration (head_dim 128, block 64/128, <=64 sequences, <=4096 blocks each)";
+    case SHPLB_E_HIP: return "HIP call or kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,320 @@
+// Block-sparse causal attention over per-row selected key blocks (gfx950).
+//
+// Work item = one (sequence, head, query block) row of the selection.  Persistent
+// workgroups draw items from a cost-descending list through one atomic ticket.
+//
+// Tiling (wave64, v_mfma_f32_32x32x16_bf16):
+//   * a workgroup is 2 waves; each wave owns BQ/2 query rows (NT = BQ/64 column
+//     tiles of 32 queries) and keeps Q as MFMA B-operands in registers;
+//   * keys are streamed in sub-tiles of 64; K goes to LDS row-major, V goes to LDS
+//     transposed ([dim][key]) so both MFMA A-operands are 16-byte LDS reads;
+//   * the first contraction is S^T = K Q^T, so a lane holds one query column: the
+//     softmax max/sum are in-lane plus one exchange with lane^32, and the
+//     probabilities feed the second contraction O^T += V^T P^T straight from
+//     registers (the key order inside a 16-key MFMA step is permuted identically
+//     on both operands, which a sum over keys does not see).
+#include "shplb_internal.h"
+
+namespace shplb {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+namespace {
+
+constexpr int kThreads = 128;
+constexpr int kKeysPerTile = 64;
+constexpr int kKRow = 136;   // halfs per K row in LDS (128 + 8 pad -> 272 B, conflict-free b128 reads)
+constexpr int kVRow = 72;    // halfs per V^T row in LDS (64 + 8 pad -> 144 B)
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  bf16x2 v = {(__bf16)a, (__bf16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// LDS column of key kk (0..63) inside a V^T row: within each group of 16 keys the
+// order is [hi][a][t] for kk = 16g + 8a + 4hi + t, matching the register layout of
+// the S^T accumulator (see the PV step).
+__device__ __forceinline__ int vt_col(int kk) {
+  return (kk & 48) | ((kk & 4) << 1) | ((kk & 8) >> 1) | (kk & 3);
+}
+
+struct TileRegs {
+  u32x4 k[8];
+  u32x2 v[4][4];
+};
+
+template <int BQ>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
+                 const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                 const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
+                 uint16_t* __restrict__ out, float* __restrict__ lse, shplb_wg_stats* __restrict__ stats,
+                 const int32_t* __restrict__ order, uint32_t* __restrict__ ticket, int32_t rows,
+                 int64_t total_tokens, float scale_log2) {
+  constexpr int NT = BQ / 64;          // 32-query column tiles per wave
+  constexpr int SUB = BQ / 64;         // 64-key sub-tiles per key block
+  constexpr int QW = 32 * NT;          // queries per wave
+
+  __shared__ __attribute__((aligned(16))) uint16_t k_lds[kKeysPerTile * kKRow];
+  __shared__ __attribute__((aligned(16))) uint16_t vt_lds[kHeadDim * kVRow];
+  __shared__ int32_t s_item;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, hi = lane >> 5;
+  const int group = meta.n_q_heads / meta.n_kv_heads;
+
+  uint32_t my_items = 0, my_cost = 0;
+  uint64_t t_first = 0, t_last = 0;
+
+  for (;;) {
+    if (tid == 0) s_item = int32_t(atomicAdd(ticket, 1u));
+    __syncthreads();
+    const int item = s_item;
+    __syncthreads();
+    if (item >= rows) break;
+    const int row = order[item];
+    int s, h, i, nb;
+    decode_row(meta, row, s, h, i, nb);
+    const int g = h / group;
+    const int seq_begin = meta.tok_begin[s], seq_end = meta.tok_begin[s + 1];
+    const int64_t sel_begin = sel_ptr[row];
+    const int n_sel = int(sel_ptr[row + 1] - sel_begin);
+    const int n_tiles = n_sel * SUB;
+    if (n_sel <= 0) continue;          // malformed row: nothing to attend to
+    if (my_items == 0) t_first = wall_clock64();
+    my_items += 1;
+    my_cost += uint32_t(n_sel);
+
+    // ---- Q fragments: B operand of S^T = K Q^T, lane (n, hi) holds dims 16ks+8hi.. of its query
+    bf16x8 qf[NT][8];
+    int q_tok[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      q_tok[nt] = seq_begin + i * BQ + wave * QW + 32 * nt + n;
+      const int tok = min(q_tok[nt], seq_end - 1);
+      const uint16_t* src = q + int64_t(tok) * st.q_t + int64_t(h) * st.q_h + 8 * hi;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) qf[nt][ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+    }
+
+    f32x16 acc_o[4][NT];
+    float m_run[NT], l_run[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      m_run[nt] = -INFINITY;
+      l_run[nt] = 0.0f;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] = 0.0f;
+    }
+
+    const uint16_t* k_head = k + int64_t(g) * st.kv_h;
+    const uint16_t* v_head = v + int64_t(g) * st.kv_h;
+
+    auto load_tile = [&](int it, TileRegs& tr) {
+      const int p = it / SUB, sub = it - p * SUB;
+      const int j = min(max(sel_idx[sel_begin + p], 0), nb - 1);
+      const int key_base = seq_begin + j * BQ + kKeysPerTile * sub;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const int x = tid + kThreads * c;
+        const int tok = min(key_base + (x >> 4), seq_end - 1);
+        tr.k[c] = *reinterpret_cast<const u32x4*>(k_head + int64_t(tok) * st.kv_t + (x & 15) * 8);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int x = tid + kThreads * c;
+        const int dg = x & 31, kg = x >> 5;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const int tok = min(key_base + 4 * kg + kk, seq_end - 1);
+          tr.v[c][kk] = *reinterpret_cast<const u32x2*>(v_head + int64_t(tok) * st.kv_t + 4 * dg);
+        }
+      }
+    };
+
+    auto store_tile = [&](const TileRegs& tr) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const int x = tid + kThreads * c;
+        *reinterpret_cast<u32x4*>(&k_lds[(x >> 4) * kKRow + (x & 15) * 8]) = tr.k[c];
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int x = tid + kThreads * c;
+        const int dg = x & 31, kg = x >> 5;
+        const int col = vt_col(4 * kg);
+        // 4 keys x 4 dims -> 4 dims x 4 keys
+#pragma unroll
+        for (int dd = 0; dd < 4; ++dd) {
+          const int w = dd >> 1;
+          u32x2 o;
+          if (dd & 1) {
+            o.x = (tr.v[c][0][w] >> 16) | (tr.v[c][1][w] & 0xffff0000u);
+            o.y = (tr.v[c][2][w] >> 16) | (tr.v[c][3][w] & 0xffff0000u);
+          } else {
+            o.x = (tr.v[c][0][w] & 0xffffu) | (tr.v[c][1][w] << 16);
+            o.y = (tr.v[c][2][w] & 0xffffu) | (tr.v[c][3][w] << 16);
+          }
+          *reinterpret_cast<u32x2*>(&vt_lds[(4 * dg + dd) * kVRow + col]) = o;
+        }
+      }
+    };
+
+    TileRegs regs;
+    load_tile(0, regs);
+    for (int it = 0; it < n_tiles; ++it) {
+      __syncthreads();                 // previous tile fully consumed
+      store_tile(regs);
+      __syncthreads();
+      const int p = it / SUB, sub = it - p * SUB;
+      const bool diag = sel_idx[sel_begin + p] == i;
+      if (it + 1 < n_tiles) load_tile(it + 1, regs);
+      // a diagonal sub-tile entirely above this wave's queries contributes nothing
+      if (diag && kKeysPerTile * sub > wave * QW + QW - 1) continue;
+
+      // ---- S^T = K Q^T : [64 keys] x [QW queries]
+      f32x16 sc[2][NT];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sc[mt][nt][r] = 0.0f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&k_lds[(32 * mt + n) * kKRow + 16 * ks + 8 * hi]);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            sc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nt][ks], sc[mt][nt], 0, 0, 0);
+        }
+      }
+
+      // ---- online softmax (log2 domain), one query column per lane
+      bf16x8 pf[NT][4];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        if (diag) {
+          const int q_in = wave * QW + 32 * nt + n;
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key_in = kKeysPerTile * sub + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
+              if (key_in > q_in) sc[mt][nt][r] = -INFINITY;
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[mt][nt][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[nt], mx * scale_log2);
+        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_use);
+        m_run[nt] = m_new;
+        float rs = 0.0f;
+        uint32_t pk[2][8];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][nt][r], scale_log2, -m_use));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][nt][r + 1], scale_log2, -m_use));
+            rs += p0 + p1;
+            pk[mt][r >> 1] = pack_bf16(p0, p1);
+          }
+        l_run[nt] = l_run[nt] * alpha + rs;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] *= alpha;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const u32x4 w = {pk[gq >> 1][4 * (gq & 1)], pk[gq >> 1][4 * (gq & 1) + 1],
+                           pk[gq >> 1][4 * (gq & 1) + 2], pk[gq >> 1][4 * (gq & 1) + 3]};
+          pf[nt][gq] = __builtin_bit_cast(bf16x8, w);
+        }
+      }
+
+      // ---- O^T += V^T P^T : [128 dims] x [QW queries], 16 keys per MFMA step
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vt_lds[(32 * dt + n) * kVRow + 16 * gq + 8 * hi]);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc_o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nt][gq], acc_o[dt][nt], 0, 0, 0);
+        }
+      }
+    }
+
+    // ---- normalise and store: lane holds, for its query, dims 32dt + 8(r/4) + 4hi + (r%4)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
+      if (q_tok[nt] < seq_end) {
+        const float inv = 1.0f / l_tot;
+        uint16_t* dst = out + int64_t(q_tok[nt]) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            u32x2 w;
+            w.x = pack_bf16(acc_o[dt][nt][4 * rq] * inv, acc_o[dt][nt][4 * rq + 1] * inv);
+            w.y = pack_bf16(acc_o[dt][nt][4 * rq + 2] * inv, acc_o[dt][nt][4 * rq + 3] * inv);
+            *reinterpret_cast<u32x2*>(dst + 32 * dt + 8 * rq) = w;
+          }
+        if (lse != nullptr && hi == 0)
+          lse[int64_t(h) * total_tokens + q_tok[nt]] =
+              (m_run[nt] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+      }
+    }
+    t_last = wall_clock64();
+  }
+
+  if (stats != nullptr && tid == 0) {
+    shplb_wg_stats rec;
+    rec.xcc_id = __builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20) & 0xf;       // XCC_ID[3:0]
+    rec.cu_id = (__builtin_amdgcn_s_getreg((16 - 1) << 11 | 0 << 6 | 4) >> 8) & 0xff; // HW_ID[15:8]
+    rec.n_items = my_items;
+    rec.cost_blocks = my_cost;
+    rec.t_first = t_first;
+    rec.t_last = t_last;
+    stats[blockIdx.x] = rec;
+  }
+}
+
+}  // namespace
+
+int32_t launch_attention(const Geometry& g, const void* q, const void* k, const void* v,
+                         const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
+                         shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
+                         int32_t n_wg, hipStream_t stream) {
+  const float scale_log2 = g.scale * 1.4426950408889634f;
+  const dim3 grid(n_wg), block(kThreads);
+  if (g.meta.block == 128)
+    hipLaunchKernelGGL(attn_kernel<128>, grid, block, 0, stream, g.meta, g.st,
+                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                       static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out),
+                       lse, stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
+  else
+    hipLaunchKernelGGL(attn_kernel<64>, grid, block, 0, stream, g.meta, g.st,
+                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                       static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out),
+                       lse, stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
+  if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
+  return SHPLB_OK;
+}
+
+}  // namespace shplb

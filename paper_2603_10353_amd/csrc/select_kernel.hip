@@ -1,0 +1,110 @@
+// Per-head top-k key-block selection: one wavefront per (sequence, head, query block) row.
+#include "shplb_internal.h"
+
+namespace shplb {
+namespace {
+
+// Monotone map float -> uint32 (larger float = larger key); +0 and -0 coincide.
+__device__ __forceinline__ uint32_t order_key(float x) {
+  x += 0.0f;                                   // -0 -> +0
+  const uint32_t b = __float_as_uint(x);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__device__ __forceinline__ int popc64(uint64_t m) { return __builtin_popcountll(m); }
+
+// SLOTS * 64 >= number of blocks of the longest sequence.
+//
+// The row keeps block 0 and block i, then the `want` best of the candidates 1..i-1
+// under the total order (score descending, index ascending).  The wave finds the
+// want-th largest key t by a 32-step bitwise search (largest t with
+// count(key >= t) >= want), takes every key > t, and fills the remainder with the
+// lowest-index keys equal to t.  Output is written in ascending block order.
+template <int SLOTS>
+__global__ __launch_bounds__(256) void select_kernel(
+    SeqMeta meta, const float* __restrict__ scores, const int64_t* __restrict__ sel_ptr,
+    int32_t* __restrict__ sel_idx, int32_t rows) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  int s, h, i, nb;
+  decode_row(meta, row, s, h, i, nb);
+  const int64_t begin = sel_ptr[row];
+  int n = int(sel_ptr[row + 1] - begin);
+  n = min(n, i + 1);                            // never more than the causal-visible blocks
+  if (n <= 0) return;
+  int32_t* out = sel_idx + begin;
+  if (lane == 0) {
+    out[0] = 0;
+    if (n >= 2) out[n - 1] = i;
+  }
+  const int want = n - 2;                       // picks among candidates 1..i-1
+  const int n_cand = i - 1;
+  if (want <= 0) return;
+  const float* srow = scores + meta.score_off[s] + (int64_t(h) * nb + i) * nb;
+
+  uint32_t key[SLOTS];
+  const int slots = (i + 63) >> 6;              // slots that hold at least one candidate
+#pragma unroll
+  for (int c = 0; c < SLOTS; ++c) {
+    const int j = c * 64 + lane;
+    key[c] = 0;                                 // 0 is below every real key (keys of finite floats are > 0)
+    if (c < slots && j >= 1 && j < i) key[c] = order_key(srow[j]);
+  }
+
+  if (want >= n_cand) {                         // budget covers every candidate
+#pragma unroll
+    for (int c = 0; c < SLOTS; ++c) {
+      const int j = c * 64 + lane;
+      if (c < slots && j >= 1 && j < i) out[j] = j;
+    }
+    return;
+  }
+
+  uint32_t t = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t probe = t | (1u << bit);
+    int cnt = 0;
+#pragma unroll
+    for (int c = 0; c < SLOTS; ++c)
+      if (c < slots) cnt += popc64(__ballot(key[c] >= probe));
+    if (cnt >= want) t = probe;
+  }
+  int above = 0;
+#pragma unroll
+  for (int c = 0; c < SLOTS; ++c)
+    if (c < slots) above += popc64(__ballot(key[c] > t));
+  const int ties_wanted = want - above;         // >= 1 by construction of t
+
+  const uint64_t below_me = (uint64_t(1) << lane) - 1;
+  int written = 0, ties_seen = 0;
+#pragma unroll
+  for (int c = 0; c < SLOTS; ++c) {
+    if (c < slots) {
+      const bool is_tie = key[c] == t;
+      const uint64_t tie_mask = __ballot(is_tie);
+      const int tie_rank = ties_seen + popc64(tie_mask & below_me);
+      const bool take = key[c] > t || (is_tie && tie_rank < ties_wanted);
+      const uint64_t take_mask = __ballot(take);
+      if (take) out[1 + written + popc64(take_mask & below_me)] = c * 64 + lane;
+      written += popc64(take_mask);
+      ties_seen += popc64(tie_mask);
+    }
+  }
+}
+
+}  // namespace
+
+int32_t launch_select(const Geometry& g, const float* scores, const int64_t* sel_ptr,
+                      int32_t* sel_idx, hipStream_t stream) {
+  const int32_t rows = int32_t(g.rows);
+  const dim3 grid((rows + 3) / 4), block(256);
+  if (g.max_nb <= 1024)
+    hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, stream, g.meta, scores, sel_ptr, sel_idx, rows);
+  else
+    hipLaunchKernelGGL(select_kernel<64>, grid, block, 0, stream, g.meta, scores, sel_ptr, sel_idx, rows);
+  if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
+  return SHPLB_OK;
+}
+
+}  // namespace shplb

@@ -1,0 +1,76 @@
+// Internal declarations shared by the translation units of libshplb (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "shplb.h"
+
+namespace shplb {
+
+constexpr int kHeadDim = 128;
+constexpr int kCostBins = 4100;       // selected-block counts 0..SHPLB_MAX_BLOCKS, rounded up
+constexpr int kOrderChunk = 256;      // rows per workgroup in the ordering kernels
+
+// Sequence geometry, passed to kernels by value (about 1 KB of kernel arguments).
+struct SeqMeta {
+  int32_t n_seq;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t block;
+  int32_t tok_begin[SHPLB_MAX_SEQ + 1];   // cu_seqlens
+  int32_t blk_begin[SHPLB_MAX_SEQ + 1];   // cumulative block counts
+  int64_t score_off[SHPLB_MAX_SEQ + 1];   // float offset of each sequence's score cube
+};
+
+struct Strides {
+  int64_t q_t, q_h, kv_t, kv_h;
+};
+
+// Validated, host-side view of a shplb_problem.
+struct Geometry {
+  SeqMeta meta;
+  Strides st;
+  int64_t total_tokens;
+  int64_t total_blocks;
+  int64_t rows;
+  int32_t max_nb;
+  float scale;
+};
+
+// Workspace carve-up (byte offsets, each 256-byte aligned).
+struct WorkspaceLayout {
+  int64_t qbar, kbar;        // fp32 [H][total_blocks][128]
+  int64_t order;             // int32 [rows]
+  int64_t hist;              // int32 [n_chunks][kCostBins]
+  int64_t bin_start;         // int32 [kCostBins]
+  int64_t ticket;            // uint32 [64] (one used; padded to its own cache lines)
+  int64_t total;
+};
+
+int32_t make_geometry(const shplb_problem* p, Geometry* g);
+WorkspaceLayout make_layout(const Geometry& g);
+int32_t persistent_workgroups();   // for the current device; <0 on HIP error
+
+// Kernel launchers (each returns a SHPLB status).
+int32_t launch_pool_scores(const Geometry& g, const void* q, const void* k, float* scores,
+                           float* qbar, float* kbar, hipStream_t stream);
+int32_t launch_select(const Geometry& g, const float* scores, const int64_t* sel_ptr,
+                      int32_t* sel_idx, hipStream_t stream);
+int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceLayout& w,
+                     char* workspace, hipStream_t stream);
+int32_t launch_attention(const Geometry& g, const void* q, const void* k, const void* v,
+                         const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
+                         shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
+                         int32_t n_wg, hipStream_t stream);
+
+// Row -> (sequence, head, query block).  Rows of one sequence are contiguous.
+__device__ __forceinline__ void decode_row(const SeqMeta& m, int32_t row, int& s, int& h, int& i, int& nb) {
+  s = 0;
+  while (s + 1 < m.n_seq && row >= m.blk_begin[s + 1] * m.n_q_heads) ++s;
+  const int local = row - m.blk_begin[s] * m.n_q_heads;
+  nb = m.blk_begin[s + 1] - m.blk_begin[s];
+  h = local / nb;
+  i = local - h * nb;
+}
+
+}  // namespace shplb

@@ -1,0 +1,111 @@
+"""GPU parity: HIP path through the C-ABI vs the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import shplb_oracle as orc
+from workloads import make_custom, make_workload
+
+from checks import SCORE_ATOL, compare_output, compare_selection
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu():
+    from harness import GpuRun
+    return GpuRun
+
+
+def full_parity(wl, softmax_scale=0.0, rows=None):
+    """scores, selection (with the near-threshold waiver), attention (oracle fed the
+    GPU's own selection) and lse, all rows unless `rows` is given."""
+    print("case", wl.name, "seqlens", np.diff(wl.cu_seqlens).tolist(), "heads", wl.n_q_heads, wl.n_kv_heads,
+          "block", wl.block, "budgets", wl.budgets.tolist()[:16], flush=True)
+    run = _gpu()(wl, softmax_scale).run_all()
+    scale = None if softmax_scale == 0.0 else softmax_scale
+    sc_o = orc.block_scores(wl.q, wl.k, wl.cu_seqlens, wl.block, scale)
+    sc_g = run.scores_host()
+    for s in range(wl.n_seq):
+        tri = np.tril_indices(sc_o[s].shape[1])
+        for h in range(wl.n_q_heads):
+            np.testing.assert_allclose(sc_g[s][h][tri], sc_o[s][h][tri], rtol=1e-5, atol=SCORE_ATOL)
+            up = np.triu_indices(sc_o[s].shape[1], 1)
+            assert np.isnan(sc_g[s][h][up]).all(), "entries above the diagonal must stay unwritten"
+    ptr_o, idx_o = orc.select_blocks(sc_o, wl.budgets)
+    np.testing.assert_array_equal(ptr_o, run.sel_ptr_host)
+    idx_g = run.sel_idx_host()
+
+    def srow(r):
+        s, h, i = orc.row_decode(wl.cu_seqlens, wl.block, wl.n_q_heads, r)
+        return sc_o[s][h, i], i
+
+    waived = compare_selection(ptr_o, idx_g, idx_o, srow,
+                               lambda r: orc.row_decode(wl.cu_seqlens, wl.block, wl.n_q_heads, r))
+    out_o, lse_o = orc.sparse_attention(wl.q, wl.k, wl.v, wl.cu_seqlens, wl.block, ptr_o, idx_g, scale, rows)
+    wa, wr = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
+    print("  waived rows %d / %d, out max abs %.3g max rel %.3g" % (waived, len(ptr_o) - 1, wa, wr), flush=True)
+    return run
+
+
+def test_config0_full():
+    run = full_parity(make_workload(0))
+    st = run.stats_host()
+    assert st["n_items"].sum() == run.rows
+    assert st["cost_blocks"].sum() == run.sel_ptr_host[-1]
+
+
+@pytest.mark.parametrize("block", [64, 128])
+def test_gqa_ragged_varlen(block):
+    # several tiles, ragged tails, a one-token sequence, a sequence shorter than a block
+    wl = make_custom([5 * block + 37, 1, block - 3, 2 * block, 3 * block + 1], 8, 2, block,
+                     [0, 1, 2, 3, 4, 5, 7, 100], seed=21 + block, name="ragged_b%d" % block)
+    full_parity(wl)
+
+
+def test_config1_shape_scaled_down():
+    # Llama-3-8B-shaped GQA layer (32/8 heads, block 128) at 4K tokens + a ragged tail
+    full_parity(make_workload(1, seqlens=[4096 + 77]))
+
+
+def test_dense_budget_equals_dense_attention():
+    wl = make_custom([1024 + 50], 4, 1, 128, [999] * 4, seed=31, name="dense")
+    run = full_parity(wl)
+    # independent check against a textbook routine on the GPU result itself
+    from workloads import f32_from_bf16_bits
+    q = torch.from_numpy(f32_from_bf16_bits(wl.q).astype(np.float64)).permute(1, 0, 2)
+    k = torch.from_numpy(f32_from_bf16_bits(wl.k).astype(np.float64)).permute(1, 0, 2).repeat_interleave(4, 0)
+    v = torch.from_numpy(f32_from_bf16_bits(wl.v).astype(np.float64)).permute(1, 0, 2).repeat_interleave(4, 0)
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True).permute(1, 0, 2).numpy()
+    compare_output(run.out_host(), ref)
+
+
+def test_explicit_softmax_scale():
+    wl = make_custom([700], 2, 2, 64, [3, 6], seed=41, name="scale")
+    full_parity(wl, softmax_scale=0.05)
+
+
+def test_select_kernel_bit_exact_on_given_scores():
+    # Same fp32 scores on both sides, many exact ties: lists must be identical.
+    wl = make_custom([64 * 70, 64 * 9 + 5], 4, 4, 64, [2, 5, 17, 64, 3, 9, 33, 1], seed=51, name="ties")
+    run = _gpu()(wl)
+    rng = np.random.default_rng(5)
+    nbs = wl.n_blocks
+    sc = [rng.integers(-3, 4, size=(4, nb, nb)).astype(np.float32) * 0.25 for nb in nbs]
+    sc[0][0, :, 3] = -0.0
+    sc[0][0, :, 5] = 0.0
+    flat = np.concatenate([x.reshape(-1) for x in sc])
+    run.select_step(torch.from_numpy(flat).to("cuda:0"))
+    torch.cuda.synchronize()
+    ptr_o, idx_o = orc.select_blocks(sc, wl.budgets)
+    np.testing.assert_array_equal(run.sel_ptr_host, ptr_o)
+    np.testing.assert_array_equal(run.sel_idx_host(), idx_o)
+
+
+def test_deterministic_across_runs():
+    wl = make_workload(1, seqlens=[2048])
+    run = _gpu()(wl).run_all()
+    o1, l1, i1 = run.out.clone(), run.lse.clone(), run.sel_idx.clone()
+    run.out.zero_(); run.lse.zero_(); run.sel_idx.fill_(-1)
+    run.run_all()
+    assert torch.equal(run.out.view(torch.int16), o1.view(torch.int16))
+    assert torch.equal(run.lse, l1) and torch.equal(run.sel_idx, i1)
