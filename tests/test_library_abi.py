@@ -1,0 +1,123 @@
+"""CPU-side checks of the boundary: the library loads, exports what the header
+declares, validates arguments, and the host-side entry points agree with the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2603_10353_amd as S
+from paper_2603_10353_amd.binding import EXPORTS
+from oracle import shplb_oracle as orc
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(S.lib_path()):
+        from paper_2603_10353_amd.build import build
+        build(verbose=False)
+
+
+def test_exports_match_header(repo_root):
+    hdr = open(os.path.join(repo_root, "include", "shplb.h")).read()
+    declared = sorted(set(re.findall(r"SHPLB_API\s+[\w\s\*]+?\b(shplb_\w+)\s*\(", hdr)))
+    assert declared == sorted(EXPORTS)
+    lib = S.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layout_matches_header():
+    from paper_2603_10353_amd.binding import _CProblem, WgStats
+    assert C.sizeof(_CProblem) == 72 and _CProblem.softmax_scale.offset == 64
+    assert C.sizeof(WgStats) == 32
+
+
+def test_shape_helpers_against_oracle():
+    cu = [0, 300, 301, 1000]
+    p = S.Problem(cu, 8, 2, 64)
+    nbs = orc.blocks_per_sequence(cu, 64)
+    assert S.shplb_num_rows(p) == 8 * sum(nbs)
+    off = S.shplb_score_layout(p)
+    assert off.tolist() == [0] + np.cumsum([8 * nb * nb for nb in nbs]).tolist()
+    rng = np.random.default_rng(0)
+    budgets = rng.integers(0, 20, size=3 * 8)
+    np.testing.assert_array_equal(S.shplb_sel_row_ptr(p, budgets), orc.sel_row_ptr(cu, 64, 8, budgets))
+    assert S.shplb_workspace_bytes(p) > 0
+
+
+def test_argument_validation():
+    ok = dict(cu_seqlens=[0, 128], n_q_heads=4, n_kv_heads=2, block=128)
+
+    def status(**kw):
+        args = dict(ok); args.update(kw)
+        try:
+            S.shplb_num_rows(S.Problem(**args))
+            return 0
+        except S.ShplbError as e:
+            return e.status
+    assert status() == 0
+    assert status(head_dim=64) == -5
+    assert status(block=32) == -5
+    assert status(n_q_heads=3) == -2
+    assert status(cu_seqlens=[1, 128]) == -2
+    assert status(cu_seqlens=[0, 128, 128]) == -2
+    assert status(cu_seqlens=list(range(0, 66 * 128, 128))) == -5       # 65 sequences
+    assert status(cu_seqlens=[0, 128 * 4097]) == -5                      # too many blocks
+    assert status(q_stride_h=100) == -2
+    assert status(q_stride_h=132) == -2                                  # not 16-byte aligned
+    assert status(softmax_scale=-1.0) == -2
+    p = S.Problem(**ok)
+    with pytest.raises(S.ShplbError) as e:
+        S.shplb_sel_row_ptr(p, [1, 2, -1, 3])
+    assert e.value.status == -3
+    # null device pointers are rejected before any device work
+    with pytest.raises(S.ShplbError) as e:
+        S.shplb_block_scores(p, None, None, None, None)
+    assert e.value.status == -1
+    with pytest.raises(S.ShplbError) as e:
+        S.shplb_sparse_attn_prefill(p, None, None, None, None, None, None)
+    assert e.value.status == -1
+    with pytest.raises(S.ShplbError) as e:
+        S.shplb_select_topk_per_head(p, None, [2, 2, 2, 2], None, None)
+    assert e.value.status == -1
+    assert "null" in S.shplb_strerror(-1) and S.shplb_strerror(0) == "ok"
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_balance_heads_bit_exact_vs_oracle(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 65))
+    parts = int(rng.integers(1, 9))
+    costs = rng.integers(0, 50 if seed % 2 else 100000, size=n)      # small range => many ties
+    part, loads = S.shplb_balance_heads(costs, parts)
+    po, lo = orc.balance_heads(costs.tolist(), parts)
+    np.testing.assert_array_equal(part, po)
+    np.testing.assert_array_equal(loads, lo)
+    cap = -(-n // parts)
+    part, loads = S.shplb_balance_heads(costs, parts, cap)
+    po, lo = orc.balance_heads(costs.tolist(), parts, cap)
+    np.testing.assert_array_equal(part, po)
+    np.testing.assert_array_equal(loads, lo)
+    assert np.bincount(part, minlength=parts).max() <= cap
+
+
+def test_balance_heads_errors_and_golden(repo_root):
+    part, loads = S.shplb_balance_heads([5, 5, 4, 4, 3, 3, 3], 3)
+    assert part.tolist() == [0, 1, 2, 2, 0, 1, 0] and loads.tolist() == [11, 8, 8]
+    for bad, code in [(dict(costs=[1, 2], n_parts=0), -2), (dict(costs=[1, -2], n_parts=2), -3),
+                      (dict(costs=[1, 2, 3], n_parts=2, max_per_part=1), -3)]:
+        with pytest.raises(S.ShplbError) as e:
+            S.shplb_balance_heads(**bad)
+        assert e.value.status == code
+    part, loads = S.shplb_balance_heads([], 3)
+    assert part.size == 0 and loads.tolist() == [0, 0, 0]
+
+
+def test_config3_share_selection():
+    # 16 KV groups of the 64-head layer -> 8 parts of 2 groups (equal-sized shares)
+    import bench
+    heads, loads = bench.pick_config3_heads(S)
+    assert len(heads) == 8 and heads[0] % 4 == 0 and heads[4] % 4 == 0
+    assert orc.imbalance(loads) < 1.35
