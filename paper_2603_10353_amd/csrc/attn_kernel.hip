@@ -4,15 +4,21 @@
 // workgroups draw items from a cost-descending list through one atomic ticket.
 //
 // Tiling (wave64, v_mfma_f32_32x32x16_bf16):
-//   * a workgroup is 2 waves; each wave owns BQ/2 query rows (NT = BQ/64 column
-//     tiles of 32 queries) and keeps Q as MFMA B-operands in registers;
-//   * keys are streamed in sub-tiles of 64; K goes to LDS row-major, V goes to LDS
-//     transposed ([dim][key]) so both MFMA A-operands are 16-byte LDS reads;
+//   * each wave owns 32*NT query rows and keeps Q as MFMA B-operands in registers;
+//     with NT = 1 a 128-row query block is 4 waves and two workgroups share a compute
+//     unit, so every SIMD holds two waves of different workgroups: one wave's softmax
+//     VALU work overlaps the other's MFMAs;
+//   * keys are streamed in sub-tiles of 64 through a double-buffered LDS stage; K is
+//     stored row-major, V transposed ([dim][key]), so both MFMA A-operands are
+//     16-byte LDS reads;
 //   * the first contraction is S^T = K Q^T, so a lane holds one query column: the
 //     softmax max/sum are in-lane plus one exchange with lane^32, and the
 //     probabilities feed the second contraction O^T += V^T P^T straight from
 //     registers (the key order inside a 16-key MFMA step is permuted identically
-//     on both operands, which a sum over keys does not see).
+//     on both operands, which a sum over keys does not see);
+//   * the running maximum is only raised (and O, l rescaled) when some row's tile
+//     maximum exceeds it by more than 2^8; in between, probabilities are taken
+//     relative to the stale maximum, which the final division by l cancels exactly.
 #include "shplb_internal.h"
 
 namespace shplb {
@@ -25,10 +31,12 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
-constexpr int kThreads = 128;
 constexpr int kKeysPerTile = 64;
 constexpr int kKRow = 136;   // halfs per K row in LDS (128 + 8 pad -> 272 B, conflict-free b128 reads)
 constexpr int kVRow = 72;    // halfs per V^T row in LDS (64 + 8 pad -> 144 B)
+constexpr int kKTile = kKeysPerTile * kKRow;
+constexpr int kVTile = kHeadDim * kVRow;
+constexpr float kRescaleSlack = 8.0f;   // log2 units a row maximum may grow before O, l are rescaled
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   bf16x2 v = {(__bf16)a, (__bf16)b};
@@ -42,25 +50,32 @@ __device__ __forceinline__ int vt_col(int kk) {
   return (kk & 48) | ((kk & 4) << 1) | ((kk & 8) >> 1) | (kk & 3);
 }
 
-struct TileRegs {
-  u32x4 k[8];
-  u32x2 v[4][4];
+template <int BQ, int NT>
+struct AttnCfg {
+  static constexpr int kWaves = BQ / (32 * NT);
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kWavesPerSimd = NT == 1 ? 2 : 1;
+  static constexpr int kKChunks = kKeysPerTile * 16 / kThreads;     // 16-byte pieces of K per thread
+  static constexpr int kVTasks = 16 * 32 / kThreads;                // 4-key x 4-dim pieces of V per thread
 };
 
-template <int BQ>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <int BQ, int NT>
+__global__ __launch_bounds__(64 * (BQ / (32 * NT)))
+__attribute__((amdgpu_waves_per_eu(NT == 1 ? 2 : 1, NT == 1 ? 2 : 1)))
 void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                  const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
                  uint16_t* __restrict__ out, float* __restrict__ lse, shplb_wg_stats* __restrict__ stats,
                  const int32_t* __restrict__ order, uint32_t* __restrict__ ticket, int32_t rows,
                  int64_t total_tokens, float scale_log2) {
-  constexpr int NT = BQ / 64;          // 32-query column tiles per wave
-  constexpr int SUB = BQ / 64;         // 64-key sub-tiles per key block
-  constexpr int QW = 32 * NT;          // queries per wave
+  using Cfg = AttnCfg<BQ, NT>;
+  constexpr int kThreads = Cfg::kThreads;
+  constexpr int SUB = BQ / kKeysPerTile;   // 64-key sub-tiles per key block
+  constexpr int QW = 32 * NT;              // queries per wave
+  constexpr int KC = Cfg::kKChunks, VT = Cfg::kVTasks;
 
-  __shared__ __attribute__((aligned(16))) uint16_t k_lds[kKeysPerTile * kKRow];
-  __shared__ __attribute__((aligned(16))) uint16_t vt_lds[kHeadDim * kVRow];
+  __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kKTile];
+  __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][kVTile];
   __shared__ int32_t s_item;
 
   const int tid = threadIdx.x;
@@ -103,10 +118,10 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     }
 
     f32x16 acc_o[4][NT];
-    float m_run[NT], l_run[NT];
+    float m_ref[NT], l_run[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      m_run[nt] = -INFINITY;
+      m_ref[nt] = -INFINITY;
       l_run[nt] = 0.0f;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
@@ -116,37 +131,39 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 
     const uint16_t* k_head = k + int64_t(g) * st.kv_h;
     const uint16_t* v_head = v + int64_t(g) * st.kv_h;
+    u32x4 k_regs[KC];
+    u32x2 v_regs[VT][4];
 
-    auto load_tile = [&](int it, TileRegs& tr) {
+    auto load_tile = [&](int it) {
       const int p = it / SUB, sub = it - p * SUB;
       const int j = min(max(sel_idx[sel_begin + p], 0), nb - 1);
       const int key_base = seq_begin + j * BQ + kKeysPerTile * sub;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
+      for (int c = 0; c < KC; ++c) {
         const int x = tid + kThreads * c;
         const int tok = min(key_base + (x >> 4), seq_end - 1);
-        tr.k[c] = *reinterpret_cast<const u32x4*>(k_head + int64_t(tok) * st.kv_t + (x & 15) * 8);
+        k_regs[c] = *reinterpret_cast<const u32x4*>(k_head + int64_t(tok) * st.kv_t + (x & 15) * 8);
       }
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < VT; ++c) {
         const int x = tid + kThreads * c;
         const int dg = x & 31, kg = x >> 5;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
           const int tok = min(key_base + 4 * kg + kk, seq_end - 1);
-          tr.v[c][kk] = *reinterpret_cast<const u32x2*>(v_head + int64_t(tok) * st.kv_t + 4 * dg);
+          v_regs[c][kk] = *reinterpret_cast<const u32x2*>(v_head + int64_t(tok) * st.kv_t + 4 * dg);
         }
       }
     };
 
-    auto store_tile = [&](const TileRegs& tr) {
+    auto store_tile = [&](int buf) {
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
+      for (int c = 0; c < KC; ++c) {
         const int x = tid + kThreads * c;
-        *reinterpret_cast<u32x4*>(&k_lds[(x >> 4) * kKRow + (x & 15) * 8]) = tr.k[c];
+        *reinterpret_cast<u32x4*>(&k_lds[buf][(x >> 4) * kKRow + (x & 15) * 8]) = k_regs[c];
       }
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < VT; ++c) {
         const int x = tid + kThreads * c;
         const int dg = x & 31, kg = x >> 5;
         const int col = vt_col(4 * kg);
@@ -156,107 +173,117 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
           const int w = dd >> 1;
           u32x2 o;
           if (dd & 1) {
-            o.x = (tr.v[c][0][w] >> 16) | (tr.v[c][1][w] & 0xffff0000u);
-            o.y = (tr.v[c][2][w] >> 16) | (tr.v[c][3][w] & 0xffff0000u);
+            o.x = (v_regs[c][0][w] >> 16) | (v_regs[c][1][w] & 0xffff0000u);
+            o.y = (v_regs[c][2][w] >> 16) | (v_regs[c][3][w] & 0xffff0000u);
           } else {
-            o.x = (tr.v[c][0][w] & 0xffffu) | (tr.v[c][1][w] << 16);
-            o.y = (tr.v[c][2][w] & 0xffffu) | (tr.v[c][3][w] << 16);
+            o.x = (v_regs[c][0][w] & 0xffffu) | (v_regs[c][1][w] << 16);
+            o.y = (v_regs[c][2][w] & 0xffffu) | (v_regs[c][3][w] << 16);
           }
-          *reinterpret_cast<u32x2*>(&vt_lds[(4 * dg + dd) * kVRow + col]) = o;
+          *reinterpret_cast<u32x2*>(&vt_lds[buf][(4 * dg + dd) * kVRow + col]) = o;
         }
       }
     };
 
-    TileRegs regs;
-    load_tile(0, regs);
+    load_tile(0);
+    store_tile(0);
+    if (n_tiles > 1) load_tile(1);
+    __syncthreads();
+
     for (int it = 0; it < n_tiles; ++it) {
-      __syncthreads();                 // previous tile fully consumed
-      store_tile(regs);
-      __syncthreads();
+      const int buf = it & 1;
+      // stage the next tile (its buffer was last read one iteration ago, before the barrier)
+      if (it + 1 < n_tiles) store_tile(buf ^ 1);
+      if (it + 2 < n_tiles) load_tile(it + 2);
+
       const int p = it / SUB, sub = it - p * SUB;
       const bool diag = sel_idx[sel_begin + p] == i;
-      if (it + 1 < n_tiles) load_tile(it + 1, regs);
       // a diagonal sub-tile entirely above this wave's queries contributes nothing
-      if (diag && kKeysPerTile * sub > wave * QW + QW - 1) continue;
+      const bool skip = diag && kKeysPerTile * sub > wave * QW + QW - 1;
+      if (!skip) {
+        const uint16_t* kt = k_lds[buf];
+        const uint16_t* vt = vt_lds[buf];
 
-      // ---- S^T = K Q^T : [64 keys] x [QW queries]
-      f32x16 sc[2][NT];
+        // ---- S^T = K Q^T : [64 keys] x [QW queries]
+        f32x16 sc[2][NT];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sc[mt][nt][r] = 0.0f;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&k_lds[(32 * mt + n) * kKRow + 16 * ks + 8 * hi]);
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
-            sc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nt][ks], sc[mt][nt], 0, 0, 0);
-        }
-      }
-
-      // ---- online softmax (log2 domain), one query column per lane
-      bf16x8 pf[NT][4];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        if (diag) {
-          const int q_in = wave * QW + 32 * nt + n;
+            for (int r = 0; r < 16; ++r) sc[mt][nt][r] = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&kt[(32 * mt + n) * kKRow + 16 * ks + 8 * hi]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              sc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nt][ks], sc[mt][nt], 0, 0, 0);
+          }
+        }
+
+        // ---- online softmax (log2 domain), one query column per lane
+        bf16x8 pf[NT][4];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          if (diag) {
+            const int q_in = wave * QW + 32 * nt + n;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int key_in = kKeysPerTile * sub + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
+                if (key_in > q_in) sc[mt][nt][r] = -INFINITY;
+              }
+          }
+          float mx = fmaxf(sc[0][nt][0], sc[1][nt][0]);
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sc[0][nt][r], sc[1][nt][r]));
+          mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+          if (__any(mx > m_ref[nt] + kRescaleSlack)) {
+            const float m_new = fmaxf(m_ref[nt], mx);
+            const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
+            m_ref[nt] = m_new;
+            l_run[nt] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] *= alpha;
+          }
+          const float m_use = m_ref[nt] == -INFINITY ? 0.0f : m_ref[nt];
+          float rs = 0.0f;
+          uint32_t pk[2][8];
 #pragma unroll
           for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int key_in = kKeysPerTile * sub + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
-              if (key_in > q_in) sc[mt][nt][r] = -INFINITY;
+            for (int r = 0; r < 16; r += 2) {
+              const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][nt][r], scale_log2, -m_use));
+              const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][nt][r + 1], scale_log2, -m_use));
+              rs += p0 + p1;
+              pk[mt][r >> 1] = pack_bf16(p0, p1);
             }
-        }
-        float mx = -INFINITY;
+          l_run[nt] += rs;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[mt][nt][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[nt], mx * scale_log2);
-        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_use);
-        m_run[nt] = m_new;
-        float rs = 0.0f;
-        uint32_t pk[2][8];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; r += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][nt][r], scale_log2, -m_use));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][nt][r + 1], scale_log2, -m_use));
-            rs += p0 + p1;
-            pk[mt][r >> 1] = pack_bf16(p0, p1);
+          for (int gq = 0; gq < 4; ++gq) {
+            const u32x4 w = {pk[gq >> 1][4 * (gq & 1)], pk[gq >> 1][4 * (gq & 1) + 1],
+                             pk[gq >> 1][4 * (gq & 1) + 2], pk[gq >> 1][4 * (gq & 1) + 3]};
+            pf[nt][gq] = __builtin_bit_cast(bf16x8, w);
           }
-        l_run[nt] = l_run[nt] * alpha + rs;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] *= alpha;
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          const u32x4 w = {pk[gq >> 1][4 * (gq & 1)], pk[gq >> 1][4 * (gq & 1) + 1],
-                           pk[gq >> 1][4 * (gq & 1) + 2], pk[gq >> 1][4 * (gq & 1) + 3]};
-          pf[nt][gq] = __builtin_bit_cast(bf16x8, w);
         }
-      }
 
-      // ---- O^T += V^T P^T : [128 dims] x [QW queries], 16 keys per MFMA step
+        // ---- O^T += V^T P^T : [128 dims] x [QW queries], 16 keys per MFMA step
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
+        for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vt_lds[(32 * dt + n) * kVRow + 16 * gq + 8 * hi]);
+          for (int gq = 0; gq < 4; ++gq) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vt[(32 * dt + n) * kVRow + 16 * gq + 8 * hi]);
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            acc_o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nt][gq], acc_o[dt][nt], 0, 0, 0);
+            for (int nt = 0; nt < NT; ++nt)
+              acc_o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nt][gq], acc_o[dt][nt], 0, 0, 0);
+          }
         }
       }
+      __syncthreads();
     }
 
     // ---- normalise and store: lane holds, for its query, dims 32dt + 8(r/4) + 4hi + (r%4)
@@ -277,7 +304,7 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
           }
         if (lse != nullptr && hi == 0)
           lse[int64_t(h) * total_tokens + q_tok[nt]] =
-              (m_run[nt] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+              (m_ref[nt] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
       }
     }
     t_last = wall_clock64();
@@ -295,24 +322,27 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   }
 }
 
+template <int BQ, int NT>
+void launch_one(const Geometry& g, const void* q, const void* k, const void* v, const int64_t* sel_ptr,
+                const int32_t* sel_idx, void* out, float* lse, shplb_wg_stats* stats,
+                const int32_t* order, uint32_t* ticket, int32_t n_wg, hipStream_t stream) {
+  const float scale_log2 = g.scale * 1.4426950408889634f;
+  hipLaunchKernelGGL((attn_kernel<BQ, NT>), dim3(n_wg), dim3(AttnCfg<BQ, NT>::kThreads), 0, stream, g.meta,
+                     g.st, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                     static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
+                     stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
+}
+
 }  // namespace
 
 int32_t launch_attention(const Geometry& g, const void* q, const void* k, const void* v,
                          const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
                          shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
                          int32_t n_wg, hipStream_t stream) {
-  const float scale_log2 = g.scale * 1.4426950408889634f;
-  const dim3 grid(n_wg), block(kThreads);
   if (g.meta.block == 128)
-    hipLaunchKernelGGL(attn_kernel<128>, grid, block, 0, stream, g.meta, g.st,
-                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
-                       static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out),
-                       lse, stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
+    launch_one<128, 1>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
   else
-    hipLaunchKernelGGL(attn_kernel<64>, grid, block, 0, stream, g.meta, g.st,
-                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
-                       static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out),
-                       lse, stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
+    launch_one<64, 1>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
   if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
   return SHPLB_OK;
 }
