@@ -26,6 +26,7 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g) {
   if (p->q_stride_t < p->q_stride_h * p->n_q_heads) return SHPLB_E_SHAPE;
   if (p->kv_stride_t < p->kv_stride_h * p->n_kv_heads) return SHPLB_E_SHAPE;
   if ((p->q_stride_t | p->q_stride_h | p->kv_stride_t | p->kv_stride_h) & 7) return SHPLB_E_SHAPE;
+  if (p->q_stride_t >= (int64_t(1) << 24) || p->kv_stride_t >= (int64_t(1) << 24)) return SHPLB_E_UNSUPPORTED;
 
   std::memset(g, 0, sizeof(*g));
   SeqMeta& m = g->meta;

@@ -8,9 +8,10 @@
 //     with NT = 1 a 128-row query block is 4 waves and two workgroups share a compute
 //     unit, so every SIMD holds two waves of different workgroups: one wave's softmax
 //     VALU work overlaps the other's MFMAs;
-//   * keys are streamed in sub-tiles of 64 through a double-buffered LDS stage; K is
-//     stored row-major, V transposed ([dim][key]), so both MFMA A-operands are
-//     16-byte LDS reads;
+//   * keys are streamed in sub-tiles of 64 through a double-buffered LDS stage; K and V
+//     are both stored row-major ([key][dim]); K is read as an MFMA A-operand with
+//     16-byte LDS reads, V through the LDS transpose read (ds_read_b64_tr_b16), which
+//     hands each lane four keys of one dim;
 //   * the first contraction is S^T = K Q^T, so a lane holds one query column: the
 //     softmax max/sum are in-lane plus one exchange with lane^32, and the
 //     probabilities feed the second contraction O^T += V^T P^T straight from
@@ -33,9 +34,9 @@ namespace {
 
 constexpr int kKeysPerTile = 64;
 constexpr int kKRow = 136;   // halfs per K row in LDS (128 + 8 pad -> 272 B, conflict-free b128 reads)
-constexpr int kVRow = 72;    // halfs per V^T row in LDS (64 + 8 pad -> 144 B)
+constexpr int kVRow = 144;   // halfs per V row in LDS (128 + 16 pad -> 288 B, conflict-free transpose reads)
 constexpr int kKTile = kKeysPerTile * kKRow;
-constexpr int kVTile = kHeadDim * kVRow;
+constexpr int kVTile = kKeysPerTile * kVRow;
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row maximum may grow before O, l are rescaled
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -43,11 +44,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-// LDS column of key kk (0..63) inside a V^T row: within each group of 16 keys the
-// order is [hi][a][t] for kk = 16g + 8a + 4hi + t, matching the register layout of
-// the S^T accumulator (see the PV step).
-__device__ __forceinline__ int vt_col(int kk) {
-  return (kk & 48) | ((kk & 4) << 1) | ((kk & 8) >> 1) | (kk & 3);
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// LDS transpose read: inside every group of 16 lanes, lane L receives element L%4 of
+// the four 8-byte pieces addressed by lanes L/4, L/4+4, L/4+8, L/4+12.
+__device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4*)(p));
 }
 
 template <int BQ, int NT>
@@ -56,7 +59,6 @@ struct AttnCfg {
   static constexpr int kThreads = 64 * kWaves;
   static constexpr int kWavesPerSimd = NT == 1 ? 2 : 1;
   static constexpr int kKChunks = kKeysPerTile * 16 / kThreads;     // 16-byte pieces of K per thread
-  static constexpr int kVTasks = 16 * 32 / kThreads;                // 4-key x 4-dim pieces of V per thread
 };
 
 template <int BQ, int NT>
@@ -72,10 +74,10 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   constexpr int kThreads = Cfg::kThreads;
   constexpr int SUB = BQ / kKeysPerTile;   // 64-key sub-tiles per key block
   constexpr int QW = 32 * NT;              // queries per wave
-  constexpr int KC = Cfg::kKChunks, VT = Cfg::kVTasks;
+  constexpr int KC = Cfg::kKChunks;
 
   __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kKTile];
-  __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][kVTile];
+  __shared__ __attribute__((aligned(16))) uint16_t v_lds[2][kVTile];
   __shared__ int32_t s_item;
 
   const int tid = threadIdx.x;
@@ -89,7 +91,7 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   for (;;) {
     if (tid == 0) s_item = int32_t(atomicAdd(ticket, 1u));
     __syncthreads();
-    const int item = s_item;
+    const int item = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
     __syncthreads();
     if (item >= rows) break;
     const int row = order[item];
@@ -129,29 +131,34 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
         for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] = 0.0f;
     }
 
-    const uint16_t* k_head = k + int64_t(g) * st.kv_h;
-    const uint16_t* v_head = v + int64_t(g) * st.kv_h;
-    u32x4 k_regs[KC];
-    u32x2 v_regs[VT][4];
+    const char* k_head = reinterpret_cast<const char*>(k + int64_t(g) * st.kv_h);
+    const char* v_head = reinterpret_cast<const char*>(v + int64_t(g) * st.kv_h);
+    const int64_t row_bytes = st.kv_t * 2;
+    // per-thread byte offsets inside a 64-key tile (constant over tiles); the tile's base
+    // and the per-chunk row steps are wave-uniform and stay in scalar registers
+    const uint32_t k_off = uint32_t((tid >> 4) * row_bytes + (tid & 15) * 16);
+    u32x4 k_regs[KC], v_regs[KC];
 
     auto load_tile = [&](int it) {
       const int p = it / SUB, sub = it - p * SUB;
       const int j = min(max(sel_idx[sel_begin + p], 0), nb - 1);
       const int key_base = seq_begin + j * BQ + kKeysPerTile * sub;
+      const int valid = seq_end - key_base;            // keys of this tile inside the sequence
+      const char* kt = k_head + int64_t(key_base) * row_bytes;
+      const char* vt = v_head + int64_t(key_base) * row_bytes;
+      if (valid >= kKeysPerTile) {
 #pragma unroll
-      for (int c = 0; c < KC; ++c) {
-        const int x = tid + kThreads * c;
-        const int tok = min(key_base + (x >> 4), seq_end - 1);
-        k_regs[c] = *reinterpret_cast<const u32x4*>(k_head + int64_t(tok) * st.kv_t + (x & 15) * 8);
-      }
+        for (int c = 0; c < KC; ++c)
+          k_regs[c] = *reinterpret_cast<const u32x4*>(kt + int64_t(c * (kThreads / 16)) * row_bytes + k_off);
 #pragma unroll
-      for (int c = 0; c < VT; ++c) {
-        const int x = tid + kThreads * c;
-        const int dg = x & 31, kg = x >> 5;
+        for (int c = 0; c < KC; ++c)
+          v_regs[c] = *reinterpret_cast<const u32x4*>(vt + int64_t(c * (kThreads / 16)) * row_bytes + k_off);
+      } else {                                          // ragged last block: clamp to the last valid key
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const int tok = min(key_base + 4 * kg + kk, seq_end - 1);
-          v_regs[c][kk] = *reinterpret_cast<const u32x2*>(v_head + int64_t(tok) * st.kv_t + 4 * dg);
+        for (int c = 0; c < KC; ++c) {
+          const int tok = min(key_base + (tid >> 4) + c * (kThreads / 16), seq_end - 1);
+          k_regs[c] = *reinterpret_cast<const u32x4*>(k_head + int64_t(tok) * row_bytes + (tid & 15) * 16);
+          v_regs[c] = *reinterpret_cast<const u32x4*>(v_head + int64_t(tok) * row_bytes + (tid & 15) * 16);
         }
       }
     };
@@ -161,28 +168,14 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       for (int c = 0; c < KC; ++c) {
         const int x = tid + kThreads * c;
         *reinterpret_cast<u32x4*>(&k_lds[buf][(x >> 4) * kKRow + (x & 15) * 8]) = k_regs[c];
-      }
-#pragma unroll
-      for (int c = 0; c < VT; ++c) {
-        const int x = tid + kThreads * c;
-        const int dg = x & 31, kg = x >> 5;
-        const int col = vt_col(4 * kg);
-        // 4 keys x 4 dims -> 4 dims x 4 keys
-#pragma unroll
-        for (int dd = 0; dd < 4; ++dd) {
-          const int w = dd >> 1;
-          u32x2 o;
-          if (dd & 1) {
-            o.x = (v_regs[c][0][w] >> 16) | (v_regs[c][1][w] & 0xffff0000u);
-            o.y = (v_regs[c][2][w] >> 16) | (v_regs[c][3][w] & 0xffff0000u);
-          } else {
-            o.x = (v_regs[c][0][w] & 0xffffu) | (v_regs[c][1][w] << 16);
-            o.y = (v_regs[c][2][w] & 0xffffu) | (v_regs[c][3][w] << 16);
-          }
-          *reinterpret_cast<u32x2*>(&vt_lds[buf][(4 * dg + dd) * kVRow + col]) = o;
-        }
+        *reinterpret_cast<u32x4*>(&v_lds[buf][(x >> 4) * kVRow + (x & 15) * 8]) = v_regs[c];
       }
     };
+
+    // transpose-read addressing of V: lane = 16*grp + 4*e + a supplies the piece
+    // (key 4*hi + e, dims 16*(grp&1) + 4a ..) and receives keys 4*hi + 0..3 of dim
+    // 16*(grp&1) + (lane&15) = lane&31, i.e. the A-operand of its own MFMA row.
+    const int v_rd = (4 * hi + ((lane >> 2) & 3)) * kVRow + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
     load_tile(0);
     store_tile(0);
@@ -201,7 +194,7 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       const bool skip = diag && kKeysPerTile * sub > wave * QW + QW - 1;
       if (!skip) {
         const uint16_t* kt = k_lds[buf];
-        const uint16_t* vt = vt_lds[buf];
+        const uint16_t* vt = v_lds[buf];
 
         // ---- S^T = K Q^T : [64 keys] x [QW queries]
         f32x16 sc[2][NT];
@@ -276,7 +269,10 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
         for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
           for (int gq = 0; gq < 4; ++gq) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vt[(32 * dt + n) * kVRow + 16 * gq + 8 * hi]);
+            // keys 16gq + 4hi + {0..3} and 16gq + 8 + 4hi + {0..3} of dim 32dt + n
+            const s16x4 lo = lds_read_tr16(&vt[v_rd + (16 * gq) * kVRow + 32 * dt]);
+            const s16x4 hi4 = lds_read_tr16(&vt[v_rd + (16 * gq + 8) * kVRow + 32 * dt]);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
               acc_o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nt][gq], acc_o[dt][nt], 0, 0, 0);
