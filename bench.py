@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM traffic of one attention launch measured with rocprofv3 --pmc (FETCH_SIZE, then
 # WRITE_SIZE), scaled by a copy kernel of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg2_llama3_8b_128k": 2 * 23702939.2 * 1024 + 1075872.5 * 1024}
 
 
 def selected_pairs(cu_seqlens, block, n_q_heads, sel_ptr_host):
@@ -113,6 +113,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run one plain 1 GiB elementwise copy kernel (reference for rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build covers one GPU's share of the path; run with --gpus 1 "
@@ -169,6 +172,13 @@ def main():
         S.shplb_sparse_attn_prefill(p, q, k, v, sel_ptr, sel_idx, out, lse, stats, ws, stream)
         if ev:
             ev[3].record()
+
+    if args.traffic_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
