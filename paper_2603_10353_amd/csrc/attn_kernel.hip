@@ -4,19 +4,23 @@
 // workgroups draw items from a cost-descending list through one atomic ticket.
 //
 // Tiling (wave64, v_mfma_f32_32x32x16_bf16):
-//   * each wave owns 32*NT query rows and keeps Q as MFMA B-operands in registers;
-//     with NT = 1 a 128-row query block is 4 waves and two workgroups share a compute
-//     unit, so every SIMD holds two waves of different workgroups: one wave's softmax
-//     VALU work overlaps the other's MFMAs;
-//   * keys are streamed in sub-tiles of 64 through a double-buffered LDS stage; K and V
-//     are both stored row-major ([key][dim]); K is read as an MFMA A-operand with
-//     16-byte LDS reads, V through the LDS transpose read (ds_read_b64_tr_b16), which
-//     hands each lane four keys of one dim;
-//   * the first contraction is S^T = K Q^T, so a lane holds one query column: the
-//     softmax max/sum are in-lane plus one exchange with lane^32, and the
-//     probabilities feed the second contraction O^T += V^T P^T straight from
-//     registers (the key order inside a 16-key MFMA step is permuted identically
-//     on both operands, which a sum over keys does not see);
+//   * a wave owns 32 query rows and keeps Q as MFMA B-operands in registers; a
+//     128-row query block is 4 waves and two workgroups share a compute unit, so every
+//     SIMD holds two waves of different workgroups: one wave's softmax VALU work
+//     overlaps the other's MFMAs;
+//   * keys are streamed in sub-tiles of 64.  K and V rows go from global memory
+//     straight into a double-buffered LDS stage (global_load_lds_dwordx4, no staging
+//     registers, no LDS store instructions).  Rows are 256 bytes, unpadded; the
+//     16-byte chunk c of row r sits at chunk slot c ^ swz(r), which keeps both the K
+//     operand reads and the V transpose reads free of bank conflicts;
+//   * the first contraction is S^T = K Q^T (A = K from LDS by 16-byte reads), so a
+//     lane holds one query column: the softmax max/sum are in-lane plus one exchange
+//     with lane^32, and the probabilities feed the second contraction
+//     O^T += V^T P^T straight from registers (the key order inside a 16-key MFMA step
+//     is permuted identically on both operands, which a sum over keys does not see);
+//     V^T operands come from the LDS transpose read (ds_read_b64_tr_b16);
+//   * all LDS operand reads of a phase are issued ahead of its MFMAs, so the MFMAs
+//     run back to back;
 //   * the running maximum is only raised (and O, l rescaled) when some row's tile
 //     maximum exceeds it by more than 2^8; in between, probabilities are taken
 //     relative to the stale maximum, which the final division by l cancels exactly.
@@ -29,61 +33,95 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
 constexpr int kKeysPerTile = 64;
-constexpr int kKRow = 136;   // halfs per K row in LDS (128 + 8 pad -> 272 B, conflict-free b128 reads)
-constexpr int kVRow = 144;   // halfs per V row in LDS (128 + 16 pad -> 288 B, conflict-free transpose reads)
-constexpr int kKTile = kKeysPerTile * kKRow;
-constexpr int kVTile = kKeysPerTile * kVRow;
+constexpr int kRowBytes = 256;                          // one key row (128 bf16) in LDS
+constexpr int kTileBytes = kKeysPerTile * kRowBytes;    // 16 KB per K or V tile
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row maximum may grow before O, l are rescaled
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   bf16x2 v = {(__bf16)a, (__bf16)b};
   return __builtin_bit_cast(uint32_t, v);
 }
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
+// Chunk swizzle of row r (only r mod 16 matters): a bijection on the 16 chunk slots.
+// Low three row bits move a chunk by pairs of slots (what the transpose reads of V
+// need: four consecutive key rows land in four different 32-byte bank groups), bit 3
+// of the row flips the slot inside the pair (sixteen consecutive K rows read by the
+// lanes of one operand fetch cover all sixteen slots).
+__device__ __forceinline__ int swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
 
 // LDS transpose read: inside every group of 16 lanes, lane L receives element L%4 of
 // the four 8-byte pieces addressed by lanes L/4, L/4+4, L/4+8, L/4+12.
-__device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (__attribute__((address_space(3))) s16x4*)(p));
+__device__ __forceinline__ s16x4 lds_read_tr16(const char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
 }
 
-template <int BQ, int NT>
-struct AttnCfg {
-  static constexpr int kWaves = BQ / (32 * NT);
-  static constexpr int kThreads = 64 * kWaves;
-  static constexpr int kWavesPerSimd = NT == 1 ? 2 : 1;
-  static constexpr int kKChunks = kKeysPerTile * 16 / kThreads;     // 16-byte pieces of K per thread
-};
+__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
 
-template <int BQ, int NT>
-__global__ __launch_bounds__(64 * (BQ / (32 * NT)))
-__attribute__((amdgpu_waves_per_eu(NT == 1 ? 2 : 1, NT == 1 ? 2 : 1)))
+// One wave copies 64 x 16 bytes from global memory (uniform base + per-lane byte
+// offset) to the 1 KB of LDS starting at lds_base: lane l's 16 bytes land at
+// lds_base + 16*l.  Issued as inline assembly so that the compiler's wait-count
+// pass does not serialise every later LDS read behind it; completion is awaited
+// explicitly (wait_vmem_all + barrier) before the stage is read.
+__device__ __forceinline__ void copy_g2l_16(const char* base, uint32_t lane_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_base), "v"(lane_off), "s"(base)
+               : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
+  return uint32_t(size_t((__attribute__((address_space(3))) const char*)(p)));
+}
+
+template <int BQ>
+__global__ __launch_bounds__(2 * BQ) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                  const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
                  uint16_t* __restrict__ out, float* __restrict__ lse, shplb_wg_stats* __restrict__ stats,
                  const int32_t* __restrict__ order, uint32_t* __restrict__ ticket, int32_t rows,
                  int64_t total_tokens, float scale_log2) {
-  using Cfg = AttnCfg<BQ, NT>;
-  constexpr int kThreads = Cfg::kThreads;
-  constexpr int SUB = BQ / kKeysPerTile;   // 64-key sub-tiles per key block
-  constexpr int QW = 32 * NT;              // queries per wave
-  constexpr int KC = Cfg::kKChunks;
+  constexpr int kWaves = BQ / 32;
+  constexpr int SUB = BQ / kKeysPerTile;            // 64-key sub-tiles per key block
+  constexpr int kRoundRows = 4 * kWaves;            // rows one round of copies moves (4 per wave)
+  constexpr int kRounds = kKeysPerTile / kRoundRows;
 
-  __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kKTile];
-  __shared__ __attribute__((aligned(16))) uint16_t v_lds[2][kVTile];
+  __shared__ __attribute__((aligned(1024))) char k_lds[2][kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char v_lds[2][kTileBytes];
   __shared__ int32_t s_item;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hi = lane >> 5;
   const int group = meta.n_q_heads / meta.n_kv_heads;
+
+  // ---- per-lane constants
+  // global->LDS copies: lane (r4 = lane>>4, slot = lane&15) of a wave fills LDS row
+  // base + r4, slot `slot`, with the source chunk slot ^ swz(row).
+  const int cp_row = 4 * wave + (lane >> 4);
+  // K operand reads: lane (n, hi) reads row 32mt + n, chunk 2ks + hi.
+  const int k_rd0 = n * kRowBytes + ((hi ^ swz(n)) << 4);                 // ks = 0; other ks: ^ (ks << 5)
+  // V transpose reads: lane = 16*grp + 4e + a supplies the piece (key 16gq + 8half + 4hi + e,
+  // dims 32dt + 16(grp&1) + 4a ..) and receives keys 4hi+0..3 (+8half, +16gq) of dim 32dt + n.
+  const int tr_e = (lane >> 2) & 3, tr_a = lane & 3, tr_mh = (lane >> 4) & 1;
+  int v_rd0[2];                                                            // dt = 0; other dt: ^ (dt << 6)
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int r = 8 * half + 4 * hi + tr_e;
+    v_rd0[half] = r * kRowBytes + (((2 * tr_mh + (tr_a >> 1)) ^ swz(r)) << 4) + 8 * (tr_a & 1);
+  }
+
+  // LDS byte offsets of this wave's 1 KB slice inside round 0 of stage 0
+  const uint32_t k_stage0 = __builtin_amdgcn_readfirstlane(lds_offset_of(&k_lds[0][0]) + 4 * wave * kRowBytes);
+  const uint32_t v_stage0 = __builtin_amdgcn_readfirstlane(lds_offset_of(&v_lds[0][0]) + 4 * wave * kRowBytes);
 
   uint32_t my_items = 0, my_cost = 0;
   uint64_t t_first = 0, t_last = 0;
@@ -107,200 +145,177 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     my_items += 1;
     my_cost += uint32_t(n_sel);
 
-    // ---- Q fragments: B operand of S^T = K Q^T, lane (n, hi) holds dims 16ks+8hi.. of its query
-    bf16x8 qf[NT][8];
-    int q_tok[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      q_tok[nt] = seq_begin + i * BQ + wave * QW + 32 * nt + n;
-      const int tok = min(q_tok[nt], seq_end - 1);
-      const uint16_t* src = q + int64_t(tok) * st.q_t + int64_t(h) * st.q_h + 8 * hi;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) qf[nt][ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
-    }
-
-    f32x16 acc_o[4][NT];
-    float m_ref[NT], l_run[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      m_ref[nt] = -INFINITY;
-      l_run[nt] = 0.0f;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] = 0.0f;
-    }
-
     const char* k_head = reinterpret_cast<const char*>(k + int64_t(g) * st.kv_h);
     const char* v_head = reinterpret_cast<const char*>(v + int64_t(g) * st.kv_h);
     const int64_t row_bytes = st.kv_t * 2;
-    // per-thread byte offsets inside a 64-key tile (constant over tiles); the tile's base
-    // and the per-chunk row steps are wave-uniform and stay in scalar registers
-    const uint32_t k_off = uint32_t((tid >> 4) * row_bytes + (tid & 15) * 16);
-    u32x4 k_regs[KC], v_regs[KC];
 
-    auto load_tile = [&](int it) {
+    // Copy tile `it` (64 keys of K and of V) from global memory into LDS stage `buf`.
+    auto issue_tile = [&](int it, int buf) {
       const int p = it / SUB, sub = it - p * SUB;
       const int j = min(max(sel_idx[sel_begin + p], 0), nb - 1);
-      const int key_base = seq_begin + j * BQ + kKeysPerTile * sub;
-      const int valid = seq_end - key_base;            // keys of this tile inside the sequence
-      const char* kt = k_head + int64_t(key_base) * row_bytes;
-      const char* vt = v_head + int64_t(key_base) * row_bytes;
-      if (valid >= kKeysPerTile) {
+      // A sub-tile that starts past the end of a ragged last block is moved back onto the
+      // last token: every row offset below must stay non-negative (it is added unsigned).
+      const int key_base = min(seq_begin + j * BQ + kKeysPerTile * sub, seq_end - 1);
+      const int last = seq_end - 1 - key_base;                 // last valid row of the tile (0 .. or >= 63)
+      const char* k_tile = k_head + int64_t(key_base) * row_bytes;
+      const char* v_tile = v_head + int64_t(key_base) * row_bytes;
+      const uint32_t k_dst = k_stage0 + buf * kTileBytes, v_dst = v_stage0 + buf * kTileBytes;
 #pragma unroll
-        for (int c = 0; c < KC; ++c)
-          k_regs[c] = *reinterpret_cast<const u32x4*>(kt + int64_t(c * (kThreads / 16)) * row_bytes + k_off);
-#pragma unroll
-        for (int c = 0; c < KC; ++c)
-          v_regs[c] = *reinterpret_cast<const u32x4*>(vt + int64_t(c * (kThreads / 16)) * row_bytes + k_off);
-      } else {                                          // ragged last block: clamp to the last valid key
-#pragma unroll
-        for (int c = 0; c < KC; ++c) {
-          const int tok = min(key_base + (tid >> 4) + c * (kThreads / 16), seq_end - 1);
-          k_regs[c] = *reinterpret_cast<const u32x4*>(k_head + int64_t(tok) * row_bytes + (tid & 15) * 16);
-          v_regs[c] = *reinterpret_cast<const u32x4*>(v_head + int64_t(tok) * row_bytes + (tid & 15) * 16);
-        }
+      for (int rd = 0; rd < kRounds; ++rd) {
+        const int r = rd * kRoundRows + cp_row;                // LDS row this lane fills
+        const int src_col = ((lane & 15) ^ swz(r)) << 4;
+        // rows past the end of the sequence (ragged last block) re-read the last valid key; they are masked
+        const uint32_t off = uint32_t(min(r, last)) * uint32_t(row_bytes) + src_col;
+        copy_g2l_16(k_tile, off, k_dst + rd * kRoundRows * kRowBytes);
+        copy_g2l_16(v_tile, off, v_dst + rd * kRoundRows * kRowBytes);
       }
     };
 
-    auto store_tile = [&](int buf) {
+    issue_tile(0, 0);
+
+    // ---- Q fragments: B operand of S^T = K Q^T, lane (n, hi) holds dims 16ks+8hi.. of its query
+    bf16x8 qf[8];
+    const int q_tok = seq_begin + i * BQ + wave * 32 + n;
+    {
+      const int tok = min(q_tok, seq_end - 1);
+      const uint16_t* src = q + int64_t(tok) * st.q_t + int64_t(h) * st.q_h + 8 * hi;
 #pragma unroll
-      for (int c = 0; c < KC; ++c) {
-        const int x = tid + kThreads * c;
-        *reinterpret_cast<u32x4*>(&k_lds[buf][(x >> 4) * kKRow + (x & 15) * 8]) = k_regs[c];
-        *reinterpret_cast<u32x4*>(&v_lds[buf][(x >> 4) * kVRow + (x & 15) * 8]) = v_regs[c];
-      }
-    };
+      for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+    }
 
-    // transpose-read addressing of V: lane = 16*grp + 4*e + a supplies the piece
-    // (key 4*hi + e, dims 16*(grp&1) + 4a ..) and receives keys 4*hi + 0..3 of dim
-    // 16*(grp&1) + (lane&15) = lane&31, i.e. the A-operand of its own MFMA row.
-    const int v_rd = (4 * hi + ((lane >> 2) & 3)) * kVRow + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-
-    load_tile(0);
-    store_tile(0);
-    if (n_tiles > 1) load_tile(1);
-    __syncthreads();
+    f32x16 acc_o[4];
+    float m_ref = -INFINITY, l_run = 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc_o[dt][r] = 0.0f;
 
     for (int it = 0; it < n_tiles; ++it) {
       const int buf = it & 1;
-      // stage the next tile (its buffer was last read one iteration ago, before the barrier)
-      if (it + 1 < n_tiles) store_tile(buf ^ 1);
-      if (it + 2 < n_tiles) load_tile(it + 2);
+      wait_vmem_all();                 // this wave's share of tile `it` has landed in LDS
+      __syncthreads();                 // ... and everyone's; everyone is also done reading stage buf^1
+      if (it + 1 < n_tiles) issue_tile(it + 1, buf ^ 1);
 
       const int p = it / SUB, sub = it - p * SUB;
       const bool diag = sel_idx[sel_begin + p] == i;
       // a diagonal sub-tile entirely above this wave's queries contributes nothing
-      const bool skip = diag && kKeysPerTile * sub > wave * QW + QW - 1;
+      const bool skip = diag && kKeysPerTile * sub > wave * 32 + 31;
       if (!skip) {
-        const uint16_t* kt = k_lds[buf];
-        const uint16_t* vt = v_lds[buf];
+        const char* kt = k_lds[buf];
+        const char* vt = v_lds[buf];
 
-        // ---- S^T = K Q^T : [64 keys] x [QW queries]
-        f32x16 sc[2][NT];
+        // ---- S^T = K Q^T : [64 keys] x [32 queries]; all 16 K operands fetched up front
+        bf16x8 kf[2][8];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
+          for (int ks = 0; ks < 8; ++ks)
+            kf[mt][ks] = *reinterpret_cast<const bf16x8*>(kt + (k_rd0 ^ (ks << 5)) + mt * 32 * kRowBytes);
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 sc[2];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sc[mt][nt][r] = 0.0f;
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
+          for (int r = 0; r < 16; ++r) sc[mt][r] = 0.0f;
 #pragma unroll
-          for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&kt[(32 * mt + n) * kKRow + 16 * ks + 8 * hi]);
+        for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-              sc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nt][ks], sc[mt][nt], 0, 0, 0);
-          }
-        }
+          for (int mt = 0; mt < 2; ++mt)
+            sc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][ks], qf[ks], sc[mt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- V^T operands for the second contraction, fetched while the softmax runs:
+        // keys 16gq + 4hi + {0..3} and 16gq + 8 + 4hi + {0..3} of dim 32dt + n
+        s16x4 vf[4][4][2];
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+              vf[gq][dt][half] = lds_read_tr16(vt + (v_rd0[half] ^ (dt << 6)) + gq * 16 * kRowBytes);
+        __builtin_amdgcn_sched_barrier(0);
 
         // ---- online softmax (log2 domain), one query column per lane
-        bf16x8 pf[NT][4];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          if (diag) {
-            const int q_in = wave * QW + 32 * nt + n;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                const int key_in = kKeysPerTile * sub + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
-                if (key_in > q_in) sc[mt][nt][r] = -INFINITY;
-              }
-          }
-          float mx = fmaxf(sc[0][nt][0], sc[1][nt][0]);
-#pragma unroll
-          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sc[0][nt][r], sc[1][nt][r]));
-          mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
-          if (__any(mx > m_ref[nt] + kRescaleSlack)) {
-            const float m_new = fmaxf(m_ref[nt], mx);
-            const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
-            m_ref[nt] = m_new;
-            l_run[nt] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] *= alpha;
-          }
-          const float m_use = m_ref[nt] == -INFINITY ? 0.0f : m_ref[nt];
-          float rs = 0.0f;
-          uint32_t pk[2][8];
+        if (diag) {
+          const int q_in = wave * 32 + n;
 #pragma unroll
           for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-              const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][nt][r], scale_log2, -m_use));
-              const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][nt][r + 1], scale_log2, -m_use));
-              rs += p0 + p1;
-              pk[mt][r >> 1] = pack_bf16(p0, p1);
+            for (int r = 0; r < 16; ++r) {
+              const int key_in = kKeysPerTile * sub + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
+              if (key_in > q_in) sc[mt][r] = -INFINITY;
             }
-          l_run[nt] += rs;
-#pragma unroll
-          for (int gq = 0; gq < 4; ++gq) {
-            const u32x4 w = {pk[gq >> 1][4 * (gq & 1)], pk[gq >> 1][4 * (gq & 1) + 1],
-                             pk[gq >> 1][4 * (gq & 1) + 2], pk[gq >> 1][4 * (gq & 1) + 3]};
-            pf[nt][gq] = __builtin_bit_cast(bf16x8, w);
-          }
         }
+        float mx = fmaxf(sc[0][0], sc[1][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sc[0][r], sc[1][r]));
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+        if (__any(mx > m_ref + kRescaleSlack)) {
+          const float m_new = fmaxf(m_ref, mx);
+          const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
+          m_ref = m_new;
+          l_run *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
+        }
+        const float m_use = m_ref == -INFINITY ? 0.0f : m_ref;
+        // exponentials first, sums and bf16 packing afterwards: no use sits right behind its exp
+        float pr[2][16];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            pr[mt][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[mt][r], scale_log2, -m_use));
+        float rs0 = 0.0f, rs1 = 0.0f;
+        uint32_t pk[2][8];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) {
+            rs0 += pr[mt][r];
+            rs1 += pr[mt][r + 1];
+            pk[mt][r >> 1] = pack_bf16(pr[mt][r], pr[mt][r + 1]);
+          }
+        const float rs = rs0 + rs1;
+        l_run += rs;
+        __builtin_amdgcn_sched_barrier(0);
 
-        // ---- O^T += V^T P^T : [128 dims] x [QW queries], 16 keys per MFMA step
+        // ---- O^T += V^T P^T : [128 dims] x [32 queries], 16 keys per MFMA step
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
+        for (int gq = 0; gq < 4; ++gq) {
+          const u32x4 w = {pk[gq >> 1][4 * (gq & 1)], pk[gq >> 1][4 * (gq & 1) + 1],
+                           pk[gq >> 1][4 * (gq & 1) + 2], pk[gq >> 1][4 * (gq & 1) + 3]};
+          const bf16x8 pf = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
-          for (int gq = 0; gq < 4; ++gq) {
-            // keys 16gq + 4hi + {0..3} and 16gq + 8 + 4hi + {0..3} of dim 32dt + n
-            const s16x4 lo = lds_read_tr16(&vt[v_rd + (16 * gq) * kVRow + 32 * dt]);
-            const s16x4 hi4 = lds_read_tr16(&vt[v_rd + (16 * gq + 8) * kVRow + 32 * dt]);
-            const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-              acc_o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nt][gq], acc_o[dt][nt], 0, 0, 0);
+          for (int dt = 0; dt < 4; ++dt) {
+            const bf16x8 a = __builtin_bit_cast(
+                bf16x8, __builtin_shufflevector(vf[gq][dt][0], vf[gq][dt][1], 0, 1, 2, 3, 4, 5, 6, 7));
+            acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, acc_o[dt], 0, 0, 0);
           }
         }
       }
-      __syncthreads();
     }
 
     // ---- normalise and store: lane holds, for its query, dims 32dt + 8(r/4) + 4hi + (r%4)
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
-      if (q_tok[nt] < seq_end) {
+    {
+      const float l_tot = l_run + __shfl_xor(l_run, 32);
+      if (q_tok < seq_end) {
         const float inv = 1.0f / l_tot;
-        uint16_t* dst = out + int64_t(q_tok[nt]) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
+        uint16_t* dst = out + int64_t(q_tok) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
             u32x2 w;
-            w.x = pack_bf16(acc_o[dt][nt][4 * rq] * inv, acc_o[dt][nt][4 * rq + 1] * inv);
-            w.y = pack_bf16(acc_o[dt][nt][4 * rq + 2] * inv, acc_o[dt][nt][4 * rq + 3] * inv);
+            w.x = pack_bf16(acc_o[dt][4 * rq] * inv, acc_o[dt][4 * rq + 1] * inv);
+            w.y = pack_bf16(acc_o[dt][4 * rq + 2] * inv, acc_o[dt][4 * rq + 3] * inv);
             *reinterpret_cast<u32x2*>(dst + 32 * dt + 8 * rq) = w;
           }
         if (lse != nullptr && hi == 0)
-          lse[int64_t(h) * total_tokens + q_tok[nt]] =
-              (m_ref[nt] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+          lse[int64_t(h) * total_tokens + q_tok] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
       }
     }
     t_last = wall_clock64();
@@ -318,13 +333,13 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   }
 }
 
-template <int BQ, int NT>
+template <int BQ>
 void launch_one(const Geometry& g, const void* q, const void* k, const void* v, const int64_t* sel_ptr,
                 const int32_t* sel_idx, void* out, float* lse, shplb_wg_stats* stats,
                 const int32_t* order, uint32_t* ticket, int32_t n_wg, hipStream_t stream) {
   const float scale_log2 = g.scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((attn_kernel<BQ, NT>), dim3(n_wg), dim3(AttnCfg<BQ, NT>::kThreads), 0, stream, g.meta,
-                     g.st, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+  hipLaunchKernelGGL((attn_kernel<BQ>), dim3(n_wg), dim3(2 * BQ), 0, stream, g.meta, g.st,
+                     static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                      static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
                      stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
 }
@@ -336,9 +351,9 @@ int32_t launch_attention(const Geometry& g, const void* q, const void* k, const 
                          shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
                          int32_t n_wg, hipStream_t stream) {
   if (g.meta.block == 128)
-    launch_one<128, 1>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
+    launch_one<128>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
   else
-    launch_one<64, 1>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
+    launch_one<64>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
   if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
   return SHPLB_OK;
 }
