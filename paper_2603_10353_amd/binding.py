@@ -55,7 +55,8 @@ WG_STATS_DTYPE = np.dtype([("xcc_id", "<u4"), ("cu_id", "<u4"), ("n_items", "<u4
 
 
 def lib_path() -> str:
-    return os.path.join(_PKG, "libshplb.so")
+    """Path of the shared library: SHPLB_LIBRARY if set, else the in-tree build."""
+    return os.environ.get("SHPLB_LIBRARY") or os.path.join(_PKG, "libshplb.so")
 
 
 def load_library():

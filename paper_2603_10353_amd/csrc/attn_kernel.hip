@@ -24,62 +24,11 @@
 //   * the running maximum is only raised (and O, l rescaled) when some row's tile
 //     maximum exceeds it by more than 2^8; in between, probabilities are taken
 //     relative to the stale maximum, which the final division by l cancels exactly.
-#include "shplb_internal.h"
+#include "attn_common.h"
 
 namespace shplb {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-
 namespace {
-
-constexpr int kKeysPerTile = 64;
-constexpr int kRowBytes = 256;                          // one key row (128 bf16) in LDS
-constexpr int kTileBytes = kKeysPerTile * kRowBytes;    // 16 KB per K or V tile
-constexpr float kRescaleSlack = 8.0f;   // log2 units a row maximum may grow before O, l are rescaled
-
-#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
-#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  bf16x2 v = {(__bf16)a, (__bf16)b};
-  return __builtin_bit_cast(uint32_t, v);
-}
-
-// Chunk swizzle of row r (only r mod 16 matters): a bijection on the 16 chunk slots.
-// Low three row bits move a chunk by pairs of slots (what the transpose reads of V
-// need: four consecutive key rows land in four different 32-byte bank groups), bit 3
-// of the row flips the slot inside the pair (sixteen consecutive K rows read by the
-// lanes of one operand fetch cover all sixteen slots).
-__device__ __forceinline__ int swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
-
-// LDS transpose read: inside every group of 16 lanes, lane L receives element L%4 of
-// the four 8-byte pieces addressed by lanes L/4, L/4+4, L/4+8, L/4+12.
-__device__ __forceinline__ s16x4 lds_read_tr16(const char* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
-}
-
-__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
-
-// One wave copies 64 x 16 bytes from global memory (uniform base + per-lane byte
-// offset) to the 1 KB of LDS starting at lds_base: lane l's 16 bytes land at
-// lds_base + 16*l.  Issued as inline assembly so that the compiler's wait-count
-// pass does not serialise every later LDS read behind it; completion is awaited
-// explicitly (wait_vmem_all + barrier) before the stage is read.
-__device__ __forceinline__ void copy_g2l_16(const char* base, uint32_t lane_off, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_base), "v"(lane_off), "s"(base)
-               : "memory", "m0");
-}
-
-__device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
-  return uint32_t(size_t((__attribute__((address_space(3))) const char*)(p)));
-}
 
 template <int BQ>
 __global__ __launch_bounds__(2 * BQ) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -351,7 +300,7 @@ int32_t launch_attention(const Geometry& g, const void* q, const void* k, const 
                          shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
                          int32_t n_wg, hipStream_t stream) {
   if (g.meta.block == 128)
-    launch_one<128>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
+    launch_attention_pipe128(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
   else
     launch_one<64>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, order, ticket, n_wg, stream);
   if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;

@@ -1,0 +1,294 @@
+// Software-pipelined block-sparse causal attention for 128-token blocks (gfx950).
+//
+// Same tiling and data layout as attn_kernel.hip (32 query rows per wave, 64-key
+// tiles, S^T = K Q^T then O^T += V^T P^T, swizzled 256-byte LDS rows filled by direct
+// global->LDS copies).  What differs is the order of work inside a wave: the
+// contraction S(t+1) = K(t+1) Q^T is issued while the exponentials of tile t run, so
+// the VALU work of the softmax executes under the wave's own MFMAs instead of waiting
+// for another wave to fill the matrix pipe:
+//
+//   iteration t:  barrier                      K(t+1), V(t) resident; stages of K(t), V(t-1) free
+//                 copies K(t+2), V(t+1) start
+//                 16 x { MFMA of S(t+1) ; exp / sum / bf16 pack of two probabilities of tile t }
+//                 16 x { MFMA of O += V(t)^T P(t)^T } with the row maxima of S(t+1) in between
+//                 raise the running maximum if some row grew by more than 2^8 (rare)
+//
+// LDS operands are fetched a few MFMAs ahead of their use.  The diagonal block's mask is
+// applied to S(t+1) before its maxima are taken.  Fully masked sub-tiles are computed
+// like any other (their probabilities are exact zeros).
+#include "attn_common.h"
+
+namespace shplb {
+namespace {
+
+constexpr int kLook = 6;   // LDS operand fetches run this many MFMAs ahead of their use
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
+                      const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                      const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
+                      uint16_t* __restrict__ out, float* __restrict__ lse,
+                      shplb_wg_stats* __restrict__ stats, const int32_t* __restrict__ order,
+                      uint32_t* __restrict__ ticket, int32_t rows, int64_t total_tokens,
+                      float scale_log2) {
+  constexpr int BQ = 128;
+  constexpr int SUB = BQ / kKeysPerTile;
+  constexpr int kRoundRows = 16;                     // rows one round of copies moves (4 per wave)
+  constexpr int kRounds = kKeysPerTile / kRoundRows;
+
+  __shared__ __attribute__((aligned(1024))) char k_lds[2][kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char v_lds[2][kTileBytes];
+  __shared__ int32_t s_item;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, hi = lane >> 5;
+  const int group = meta.n_q_heads / meta.n_kv_heads;
+  const int64_t row_bytes = st.kv_t * 2;
+
+  // ---- per-lane constants (see attn_kernel.hip for the layouts)
+  const int cp_row = 4 * wave + (lane >> 4);
+  const uint32_t cp_off = uint32_t(cp_row) * uint32_t(row_bytes) + (((lane & 15) ^ swz(cp_row)) << 4);
+  const int k_rd0 = n * kRowBytes + ((hi ^ swz(n)) << 4);
+  const int tr_e = (lane >> 2) & 3, tr_a = lane & 3, tr_mh = (lane >> 4) & 1;
+  int v_rd0[2];
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int r = 8 * half + 4 * hi + tr_e;
+    v_rd0[half] = r * kRowBytes + (((2 * tr_mh + (tr_a >> 1)) ^ swz(r)) << 4) + 8 * (tr_a & 1);
+  }
+  const uint32_t k_stage0 = __builtin_amdgcn_readfirstlane(lds_offset_of(&k_lds[0][0]) + 4 * wave * kRowBytes);
+  const uint32_t v_stage0 = __builtin_amdgcn_readfirstlane(lds_offset_of(&v_lds[0][0]) + 4 * wave * kRowBytes);
+
+  uint32_t my_items = 0, my_cost = 0;
+  uint64_t t_first = 0, t_last = 0;
+
+  for (;;) {
+    if (tid == 0) s_item = int32_t(atomicAdd(ticket, 1u));
+    __syncthreads();
+    const int item = __builtin_amdgcn_readfirstlane(s_item);
+    __syncthreads();
+    if (item >= rows) break;
+    const int row = order[item];
+    int s, h, i, nb;
+    decode_row(meta, row, s, h, i, nb);
+    const int g = h / group;
+    const int seq_begin = meta.tok_begin[s], seq_end = meta.tok_begin[s + 1];
+    const int64_t sel_begin = sel_ptr[row];
+    const int n_sel = int(sel_ptr[row + 1] - sel_begin);
+    const int n_tiles = n_sel * SUB;
+    if (n_sel <= 0) continue;
+    if (my_items == 0) t_first = wall_clock64();
+    my_items += 1;
+    my_cost += uint32_t(n_sel);
+
+    const char* k_head = reinterpret_cast<const char*>(k + int64_t(g) * st.kv_h);
+    const char* v_head = reinterpret_cast<const char*>(v + int64_t(g) * st.kv_h);
+
+    // Copy the K or V part of tile t into LDS stage `stage`.
+    auto issue = [&](const char* head, uint32_t stage0, int t, int stage) {
+      const int j = min(max(sel_idx[sel_begin + (t >> 1)], 0), nb - 1);
+      // a sub-tile that starts past the end of a ragged last block is moved back onto the
+      // last token: row offsets must stay non-negative (they are added unsigned)
+      const int key_base = min(seq_begin + j * BQ + kKeysPerTile * (t & 1), seq_end - 1);
+      const int last = seq_end - 1 - key_base;
+      const char* tile = head + int64_t(key_base) * row_bytes;
+      const uint32_t dst = stage0 + stage * kTileBytes;
+      if (last >= kKeysPerTile - 1) {
+#pragma unroll
+        for (int rd = 0; rd < kRounds; ++rd)
+          copy_g2l_16(tile + int64_t(rd * kRoundRows) * row_bytes, cp_off, dst + rd * kRoundRows * kRowBytes);
+      } else {                                     // ragged: rows past the end re-read the last valid key (masked)
+#pragma unroll
+        for (int rd = 0; rd < kRounds; ++rd) {
+          const int r = rd * kRoundRows + cp_row;
+          const uint32_t off = uint32_t(min(r, last)) * uint32_t(row_bytes) + (((lane & 15) ^ swz(r)) << 4);
+          copy_g2l_16(tile, off, dst + rd * kRoundRows * kRowBytes);
+        }
+      }
+    };
+    auto is_diag = [&](int t) { return sel_idx[sel_begin + (t >> 1)] == i; };
+
+    issue(k_head, k_stage0, 0, 0);
+    issue(v_head, v_stage0, 0, 0);
+    if (n_tiles > 1) issue(k_head, k_stage0, 1, 1);
+
+    // ---- Q fragments: B operand of S^T = K Q^T, lane (n, hi) holds dims 16ks+8hi.. of its query
+    bf16x8 qf[8];
+    const int q_tok = seq_begin + i * BQ + wave * 32 + n;
+    {
+      const int tok = min(q_tok, seq_end - 1);
+      const uint16_t* src = q + int64_t(tok) * st.q_t + int64_t(h) * st.q_h + 8 * hi;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+    }
+
+    f32x16 acc_o[4];
+    float m_ref = -INFINITY, l_run = 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc_o[dt][r] = 0.0f;
+
+    // Mask (diagonal block only), row maxima and the rare raise of the running maximum.
+    auto finish_scores = [&](f32x16 (&sc)[2], int t) {
+      if (is_diag(t)) {
+        const int q_in = wave * 32 + n;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key_in = kKeysPerTile * (t & 1) + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
+            if (key_in > q_in) sc[mt][r] = -INFINITY;
+          }
+      }
+      float mx = fmaxf(sc[0][0], sc[1][0]);
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sc[0][r], sc[1][r]));
+      mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+      if (__any(mx > m_ref + kRescaleSlack)) {
+        const float m_new = fmaxf(m_ref, mx);
+        const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
+        m_ref = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
+      }
+    };
+
+    auto read_k = [&](const char* kt, int gi) {       // operand of QK MFMA gi = 2*ks + mt
+      return *reinterpret_cast<const bf16x8*>(kt + (k_rd0 ^ ((gi >> 1) << 5)) + (gi & 1) * 32 * kRowBytes);
+    };
+    auto read_v = [&](const char* vt, int gi) {       // operand of PV MFMA gi = 4*gq + dt
+      const int gq = gi >> 2, dt = gi & 3;
+      const s16x4 lo = lds_read_tr16(vt + (v_rd0[0] ^ (dt << 6)) + gq * 16 * kRowBytes);
+      const s16x4 up = lds_read_tr16(vt + (v_rd0[1] ^ (dt << 6)) + gq * 16 * kRowBytes);
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    // ---- prologue: S(0)
+    f32x16 sc_cur[2];
+    wait_vmem_all();
+    __syncthreads();
+    {
+      const char* kt = k_lds[0];
+      bf16x8 kf[16];
+#pragma unroll
+      for (int gi = 0; gi < 16; ++gi) kf[gi] = read_k(kt, gi);
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc_cur[mt][r] = 0.0f;
+#pragma unroll
+      for (int gi = 0; gi < 16; ++gi)
+        sc_cur[gi & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[gi >> 1], sc_cur[gi & 1], 0, 0, 0);
+      finish_scores(sc_cur, 0);
+    }
+
+    for (int t = 0; t < n_tiles; ++t) {
+      const bool has_next = t + 1 < n_tiles;
+      wait_vmem_all();                  // own copies of K(t+1), V(t) have landed
+      __syncthreads();                  // everyone's have; stages of K(t) and V(t-1) are free
+      if (t + 2 < n_tiles) issue(k_head, k_stage0, t + 2, t & 1);
+      if (has_next) issue(v_head, v_stage0, t + 1, (t + 1) & 1);
+
+      const char* kn = k_lds[(t + 1) & 1];
+      const char* vc = v_lds[t & 1];
+      const float m_use = m_ref == -INFINITY ? 0.0f : m_ref;
+
+      bf16x8 kf[16], vf[16];
+      f32x16 sc_nxt[2];
+      uint32_t pk[2][8];
+      float rs0 = 0.0f, rs1 = 0.0f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc_nxt[mt][r] = 0.0f;
+
+      // ---- S(t+1) under the exponentials of tile t
+#pragma unroll
+      for (int gi = 0; gi < kLook; ++gi) kf[gi] = read_k(kn, gi);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int gi = 0; gi < 16; ++gi) {
+        if (gi + kLook < 16) kf[gi + kLook] = read_k(kn, gi + kLook);
+        else vf[gi + kLook - 16] = read_v(vc, gi + kLook - 16);
+        sc_nxt[gi & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[gi >> 1], sc_nxt[gi & 1], 0, 0, 0);
+        {
+          const int mt = gi >> 3, r = 2 * (gi & 7);
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][r], scale_log2, -m_use));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][r + 1], scale_log2, -m_use));
+          rs0 += p0;
+          rs1 += p1;
+          pk[mt][gi & 7] = pack_bf16(p0, p1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      l_run += rs0 + rs1;
+
+      // ---- O^T += V(t)^T P(t)^T
+#pragma unroll
+      for (int gi = 0; gi < 16; ++gi) {
+        if (gi + kLook < 16) vf[gi + kLook] = read_v(vc, gi + kLook);
+        const int gq = gi >> 2, dt = gi & 3;
+        const u32x4 w = {pk[gq >> 1][4 * (gq & 1)], pk[gq >> 1][4 * (gq & 1) + 1],
+                         pk[gq >> 1][4 * (gq & 1) + 2], pk[gq >> 1][4 * (gq & 1) + 3]};
+        acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[gi], __builtin_bit_cast(bf16x8, w), acc_o[dt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+
+      if (has_next) finish_scores(sc_nxt, t + 1);
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) sc_cur[mt] = sc_nxt[mt];
+    }
+
+    // ---- normalise and store: lane holds, for its query, dims 32dt + 8(r/4) + 4hi + (r%4)
+    {
+      const float l_tot = l_run + __shfl_xor(l_run, 32);
+      if (q_tok < seq_end) {
+        const float inv = 1.0f / l_tot;
+        uint16_t* dst = out + int64_t(q_tok) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            u32x2 w;
+            w.x = pack_bf16(acc_o[dt][4 * rq] * inv, acc_o[dt][4 * rq + 1] * inv);
+            w.y = pack_bf16(acc_o[dt][4 * rq + 2] * inv, acc_o[dt][4 * rq + 3] * inv);
+            *reinterpret_cast<u32x2*>(dst + 32 * dt + 8 * rq) = w;
+          }
+        if (lse != nullptr && hi == 0)
+          lse[int64_t(h) * total_tokens + q_tok] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+      }
+    }
+    t_last = wall_clock64();
+  }
+
+  if (stats != nullptr && tid == 0) {
+    shplb_wg_stats rec;
+    rec.xcc_id = __builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20) & 0xf;       // XCC_ID[3:0]
+    rec.cu_id = (__builtin_amdgcn_s_getreg((16 - 1) << 11 | 0 << 6 | 4) >> 8) & 0xff; // HW_ID[15:8]
+    rec.n_items = my_items;
+    rec.cost_blocks = my_cost;
+    rec.t_first = t_first;
+    rec.t_last = t_last;
+    stats[blockIdx.x] = rec;
+  }
+}
+
+}  // namespace
+
+void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
+                              const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
+                              shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
+                              int32_t n_wg, hipStream_t stream) {
+  const float scale_log2 = g.scale * 1.4426950408889634f;
+  hipLaunchKernelGGL(attn_pipe_kernel, dim3(n_wg), dim3(256), 0, stream, g.meta, g.st,
+                     static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                     static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
+                     stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
+}
+
+}  // namespace shplb

@@ -63,6 +63,12 @@ int32_t launch_attention(const Geometry& g, const void* q, const void* k, const 
                          shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
                          int32_t n_wg, hipStream_t stream);
 
+// Pipelined variant for 128-token blocks (attn_pipe_kernel.hip).
+void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
+                              const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
+                              shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
+                              int32_t n_wg, hipStream_t stream);
+
 // Row -> (sequence, head, query block).  Rows of one sequence are contiguous.
 __device__ __forceinline__ void decode_row(const SeqMeta& m, int32_t row, int& s, int& h, int& i, int& nb) {
   s = 0;
