@@ -52,6 +52,34 @@ __device__ __forceinline__ void copy_g2l_16(const char* base, uint32_t lane_off,
                : "memory", "m0");
 }
 
+// acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1)).
+__device__ __forceinline__ float dot2_ones(uint32_t packed, float acc) {
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), ones, acc, false);
+}
+
+// Exchange with lane ^ 32 without going through LDS.  v_permlane32_swap exchanges the
+// upper half of its first register with the lower half of its second; fed two copies
+// of x it leaves {x of the lower lane, x of the upper lane} of the pair in every lane.
+// (Written as assembly: the two results must be two distinct registers.  The leading
+// s_nop covers the wait states the swap needs after a VALU write of its operands.)
+__device__ __forceinline__ void pair_values(float x, float& lower, float& upper) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  lower = a;
+  upper = b;
+}
+__device__ __forceinline__ float pair_max(float x) {
+  float a, b;
+  pair_values(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  float a, b;
+  pair_values(x, a, b);
+  return a + b;
+}
+
 __device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
   return uint32_t(size_t((__attribute__((address_space(3))) const char*)(p)));
 }

@@ -1,29 +1,36 @@
 // Software-pipelined block-sparse causal attention for 128-token blocks (gfx950).
 //
-// Same tiling and data layout as attn_kernel.hip (32 query rows per wave, 64-key
-// tiles, S^T = K Q^T then O^T += V^T P^T, swizzled 256-byte LDS rows filled by direct
-// global->LDS copies).  What differs is the order of work inside a wave: the
-// contraction S(t+1) = K(t+1) Q^T is issued while the exponentials of tile t run, so
-// the VALU work of the softmax executes under the wave's own MFMAs instead of waiting
-// for another wave to fill the matrix pipe:
+// Same data layout as attn_kernel.hip (64-key tiles, S^T = K Q^T then O^T += V^T P^T,
+// swizzled 256-byte LDS rows filled by direct global->LDS copies).  What differs:
 //
-//   iteration t:  barrier                      K(t+1), V(t) resident; stages of K(t), V(t-1) free
-//                 copies K(t+2), V(t+1) start
-//                 16 x { MFMA of S(t+1) ; exp / sum / bf16 pack of two probabilities of tile t }
-//                 16 x { MFMA of O += V(t)^T P(t)^T } with the row maxima of S(t+1) in between
-//                 raise the running maximum if some row grew by more than 2^8 (rare)
+//   * a wave owns 32*NT query rows.  With NT = 2 a 128-row query block is two waves of
+//     64 rows, every K / V operand fetched from LDS feeds two MFMAs (half the LDS read
+//     traffic of the 32-row layout), and a wave may use the full 512-entry register
+//     file (one wave per SIMD, two workgroups per compute unit);
+//   * the order of work inside a wave: the contraction S(t+1) = K(t+1) Q^T is issued
+//     while the exponentials of tile t run, and the row maxima of S(t+1) are taken
+//     between the MFMAs of O += V(t)^T P(t)^T, so the softmax VALU work executes under
+//     the wave's own MFMAs:
 //
-// LDS operands are fetched a few MFMAs ahead of their use.  The diagonal block's mask is
-// applied to S(t+1) before its maxima are taken.  Fully masked sub-tiles are computed
-// like any other (their probabilities are exact zeros).
+//       step t:  barrier                      K(t+1), V(t) resident; stages of K(t), V(t-1) free
+//                copies K(t+2), V(t+1) start
+//                16 x { NT MFMAs of S(t+1) ; exp / sum / bf16 pack of 2*NT probabilities of tile t }
+//                mask S(t+1) if it is the diagonal block
+//                16 x { NT MFMAs of O += V(t)^T P(t)^T ; one step of the row maxima of S(t+1) }
+//                raise the running maximum if some row grew by more than 2^8 (rare)
+//
+// The two score buffers swap roles from step to step (the tile count is even, steps are
+// issued in pairs).  LDS operands are fetched kLook groups ahead of their use.  Fully
+// masked sub-tiles are computed like any other (their probabilities are exact zeros).
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace shplb {
 namespace {
 
-constexpr int kLook = 6;   // LDS operand fetches run this many MFMAs ahead of their use
-
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int NT>
+__global__ __launch_bounds__(256 / NT) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 2 : 1, NT == 1 ? 2 : 1)))
 void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                       const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                       const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
@@ -32,9 +39,11 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                       uint32_t* __restrict__ ticket, int32_t rows, int64_t total_tokens,
                       float scale_log2) {
   constexpr int BQ = 128;
-  constexpr int SUB = BQ / kKeysPerTile;
-  constexpr int kRoundRows = 16;                     // rows one round of copies moves (4 per wave)
+  constexpr int kWaves = 4 / NT;
+  constexpr int QW = 32 * NT;                        // query rows per wave
+  constexpr int kRoundRows = 4 * kWaves;             // rows one round of copies moves (4 per wave)
   constexpr int kRounds = kKeysPerTile / kRoundRows;
+  constexpr int kLook = NT == 1 ? 6 : 8;             // LDS operand fetches run this many groups ahead
 
   __shared__ __attribute__((aligned(1024))) char k_lds[2][kTileBytes];
   __shared__ __attribute__((aligned(1024))) char v_lds[2][kTileBytes];
@@ -47,8 +56,12 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   const int64_t row_bytes = st.kv_t * 2;
 
   // ---- per-lane constants (see attn_kernel.hip for the layouts)
+  // copies: in round rd this lane fills LDS row rd*kRoundRows + cp_row, slot lane&15, with
+  // source chunk slot ^ swz(row).  Rounds of 8 rows alternate bit 3 of the row, which
+  // flips the low bit of the swizzle: two per-lane source offsets cover all rounds.
   const int cp_row = 4 * wave + (lane >> 4);
-  const uint32_t cp_off = uint32_t(cp_row) * uint32_t(row_bytes) + (((lane & 15) ^ swz(cp_row)) << 4);
+  const uint32_t cp_off0 = uint32_t(cp_row) * uint32_t(row_bytes) + (((lane & 15) ^ swz(cp_row)) << 4);
+  const uint32_t cp_off1 = uint32_t(cp_row) * uint32_t(row_bytes) + (((lane & 15) ^ swz(cp_row) ^ 1) << 4);
   const int k_rd0 = n * kRowBytes + ((hi ^ swz(n)) << 4);
   const int tr_e = (lane >> 2) & 3, tr_a = lane & 3, tr_mh = (lane >> 4) & 1;
   int v_rd0[2];
@@ -76,7 +89,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     const int seq_begin = meta.tok_begin[s], seq_end = meta.tok_begin[s + 1];
     const int64_t sel_begin = sel_ptr[row];
     const int n_sel = int(sel_ptr[row + 1] - sel_begin);
-    const int n_tiles = n_sel * SUB;
+    const int n_tiles = n_sel * 2;                     // two 64-key tiles per 128-token block: always even
     if (n_sel <= 0) continue;
     if (my_items == 0) t_first = wall_clock64();
     my_items += 1;
@@ -85,9 +98,9 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     const char* k_head = reinterpret_cast<const char*>(k + int64_t(g) * st.kv_h);
     const char* v_head = reinterpret_cast<const char*>(v + int64_t(g) * st.kv_h);
 
-    // Copy the K or V part of tile t into LDS stage `stage`.
-    auto issue = [&](const char* head, uint32_t stage0, int t, int stage) {
-      const int j = min(max(sel_idx[sel_begin + (t >> 1)], 0), nb - 1);
+    // Copy the K or V rows of tile t into LDS stage `stage`.
+    auto issue = [&](const char* head, uint32_t stage0, int t, int stage, int j_raw) {
+      const int j = min(max(j_raw, 0), nb - 1);
       // a sub-tile that starts past the end of a ragged last block is moved back onto the
       // last token: row offsets must stay non-negative (they are added unsigned)
       const int key_base = min(seq_begin + j * BQ + kKeysPerTile * (t & 1), seq_end - 1);
@@ -96,8 +109,11 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       const uint32_t dst = stage0 + stage * kTileBytes;
       if (last >= kKeysPerTile - 1) {
 #pragma unroll
-        for (int rd = 0; rd < kRounds; ++rd)
-          copy_g2l_16(tile + int64_t(rd * kRoundRows) * row_bytes, cp_off, dst + rd * kRoundRows * kRowBytes);
+        for (int rd = 0; rd < kRounds; ++rd) {
+          const bool odd8 = ((rd * kRoundRows) >> 3) & 1;       // round starts at an odd multiple of 8 rows
+          copy_g2l_16(tile + int64_t(rd * kRoundRows) * row_bytes, odd8 ? cp_off1 : cp_off0,
+                      dst + rd * kRoundRows * kRowBytes);
+        }
       } else {                                     // ragged: rows past the end re-read the last valid key (masked)
 #pragma unroll
         for (int rd = 0; rd < kRounds; ++rd) {
@@ -107,61 +123,83 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
         }
       }
     };
-    auto is_diag = [&](int t) { return sel_idx[sel_begin + (t >> 1)] == i; };
+    // selected block of tile pair b (tiles 2b, 2b+1); read one pair ahead of its first use so
+    // that the scalar-memory latency never sits in front of a copy
+    auto block_of = [&](int b) { return sel_idx[sel_begin + min(b, n_sel - 1)]; };
+    int j0 = block_of(0), j1 = block_of(1);
 
-    issue(k_head, k_stage0, 0, 0);
-    issue(v_head, v_stage0, 0, 0);
-    if (n_tiles > 1) issue(k_head, k_stage0, 1, 1);
+    issue(k_head, k_stage0, 0, 0, j0);
+    issue(v_head, v_stage0, 0, 0, j0);
+    issue(k_head, k_stage0, 1, 1, j0);
 
     // ---- Q fragments: B operand of S^T = K Q^T, lane (n, hi) holds dims 16ks+8hi.. of its query
-    bf16x8 qf[8];
-    const int q_tok = seq_begin + i * BQ + wave * 32 + n;
-    {
-      const int tok = min(q_tok, seq_end - 1);
+    bf16x8 qf[NT][8];
+    int q_tok[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      q_tok[nt] = seq_begin + i * BQ + wave * QW + 32 * nt + n;
+      const int tok = min(q_tok[nt], seq_end - 1);
       const uint16_t* src = q + int64_t(tok) * st.q_t + int64_t(h) * st.q_h + 8 * hi;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+      for (int ks = 0; ks < 8; ++ks) qf[nt][ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
     }
 
-    f32x16 acc_o[4];
-    float m_ref = -INFINITY, l_run = 0.0f;
+    f32x16 acc_o[4][NT];
+    float m_ref[NT], l_run[NT];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int nt = 0; nt < NT; ++nt) {
+      m_ref[nt] = -INFINITY;
+      l_run[nt] = 0.0f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc_o[dt][r] = 0.0f;
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] = 0.0f;
+    }
 
-    // Mask (diagonal block only), row maxima and the rare raise of the running maximum.
-    auto finish_scores = [&](f32x16 (&sc)[2], int t) {
-      if (is_diag(t)) {
-        const int q_in = wave * 32 + n;
+    auto mask_scores = [&](f32x16 (&sc)[2][NT], int t) {          // diagonal block: keys above the query
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int q_in = wave * QW + 32 * nt + n;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int key_in = kKeysPerTile * (t & 1) + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
-            if (key_in > q_in) sc[mt][r] = -INFINITY;
+            if (key_in > q_in) sc[mt][nt][r] = -INFINITY;
           }
       }
-      float mx = fmaxf(sc[0][0], sc[1][0]);
+    };
+    // mx[nt] = in-lane maximum of the tile's scores; raise the running maximum when needed
+    auto settle_max = [&](float (&mx)[NT]) {
+      bool grow = false;
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sc[0][r], sc[1][r]));
-      mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
-      if (__any(mx > m_ref + kRescaleSlack)) {
-        const float m_new = fmaxf(m_ref, mx);
-        const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
-        m_ref = m_new;
-        l_run *= alpha;
+      for (int nt = 0; nt < NT; ++nt) {
+#ifdef SHPLB_EXP_SHFL_MAX
+        mx[nt] = fmaxf(mx[nt], __shfl_xor(mx[nt], 32)) * scale_log2;
+#else
+        mx[nt] = pair_max(mx[nt]) * scale_log2;
+#endif
+        grow = grow || (mx[nt] > m_ref[nt] + kRescaleSlack);
+      }
+      if (__any(grow)) {
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int nt = 0; nt < NT; ++nt) {
+          const float m_new = fmaxf(m_ref[nt], mx[nt]);
+          const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
+          m_ref[nt] = m_new;
+          l_run[nt] *= alpha;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
+          for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] *= alpha;
+        }
       }
     };
 
-    auto read_k = [&](const char* kt, int gi) {       // operand of QK MFMA gi = 2*ks + mt
+    auto read_k = [&](const char* kt, int gi) {       // operand of QK group gi = 2*ks + mt
       return *reinterpret_cast<const bf16x8*>(kt + (k_rd0 ^ ((gi >> 1) << 5)) + (gi & 1) * 32 * kRowBytes);
     };
-    auto read_v = [&](const char* vt, int gi) {       // operand of PV MFMA gi = 4*gq + dt
+    auto read_v = [&](const char* vt, int gi) {       // operand of PV group gi = 4*gq + dt
       const int gq = gi >> 2, dt = gi & 3;
       const s16x4 lo = lds_read_tr16(vt + (v_rd0[0] ^ (dt << 6)) + gq * 16 * kRowBytes);
       const s16x4 up = lds_read_tr16(vt + (v_rd0[1] ^ (dt << 6)) + gq * 16 * kRowBytes);
@@ -169,7 +207,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     };
 
     // ---- prologue: S(0)
-    f32x16 sc_cur[2];
+    f32x16 sc_a[2][NT], sc_b[2][NT];
     wait_vmem_all();
     __syncthreads();
     {
@@ -180,87 +218,151 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sc_cur[mt][r] = 0.0f;
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sc_a[mt][nt][r] = 0.0f;
 #pragma unroll
       for (int gi = 0; gi < 16; ++gi)
-        sc_cur[gi & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[gi >> 1], sc_cur[gi & 1], 0, 0, 0);
-      finish_scores(sc_cur, 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          sc_a[gi & 1][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[nt][gi >> 1], sc_a[gi & 1][nt], 0, 0, 0);
+      if (j0 == i) mask_scores(sc_a, 0);
+      float mx[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        mx[nt] = fmaxf(sc_a[0][nt][0], sc_a[1][nt][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx[nt] = fmaxf(mx[nt], fmaxf(sc_a[0][nt][r], sc_a[1][nt][r]));
+      }
+      settle_max(mx);
     }
 
-    for (int t = 0; t < n_tiles; ++t) {
-      const bool has_next = t + 1 < n_tiles;
+    // One step: tile t's softmax and PV from sc_cur, tile t+1's scores into sc_nxt.
+    // jv / jk: selected blocks of tiles t+1 and t+2.
+    auto step = [&](auto has_next_c, f32x16 (&sc_cur)[2][NT], f32x16 (&sc_nxt)[2][NT], int t, int jv, int jk) {
+      constexpr bool kHasNext = decltype(has_next_c)::value;
       wait_vmem_all();                  // own copies of K(t+1), V(t) have landed
       __syncthreads();                  // everyone's have; stages of K(t) and V(t-1) are free
-      if (t + 2 < n_tiles) issue(k_head, k_stage0, t + 2, t & 1);
-      if (has_next) issue(v_head, v_stage0, t + 1, (t + 1) & 1);
+      if (t + 2 < n_tiles) issue(k_head, k_stage0, t + 2, t & 1, jk);
+      if (kHasNext) issue(v_head, v_stage0, t + 1, (t + 1) & 1, jv);
 
       const char* kn = k_lds[(t + 1) & 1];
       const char* vc = v_lds[t & 1];
-      const float m_use = m_ref == -INFINITY ? 0.0f : m_ref;
+      float m_use[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) m_use[nt] = m_ref[nt] == -INFINITY ? 0.0f : m_ref[nt];
 
       bf16x8 kf[16], vf[16];
-      f32x16 sc_nxt[2];
-      uint32_t pk[2][8];
-      float rs0 = 0.0f, rs1 = 0.0f;
+      uint32_t pk[NT][2][8];
+      float rs0[NT], rs1[NT];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int nt = 0; nt < NT; ++nt) rs0[nt] = rs1[nt] = 0.0f;
+      if (kHasNext) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sc_nxt[mt][r] = 0.0f;
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc_nxt[mt][nt][r] = 0.0f;
+      }
 
       // ---- S(t+1) under the exponentials of tile t
+      if (kHasNext) {
 #pragma unroll
-      for (int gi = 0; gi < kLook; ++gi) kf[gi] = read_k(kn, gi);
+        for (int gi = 0; gi < kLook; ++gi) kf[gi] = read_k(kn, gi);
+      } else {
+#pragma unroll
+        for (int gi = 0; gi < kLook; ++gi) vf[gi] = read_v(vc, gi);
+      }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int gi = 0; gi < 16; ++gi) {
-        if (gi + kLook < 16) kf[gi + kLook] = read_k(kn, gi + kLook);
-        else vf[gi + kLook - 16] = read_v(vc, gi + kLook - 16);
-        sc_nxt[gi & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[gi >> 1], sc_nxt[gi & 1], 0, 0, 0);
-        {
+        if (kHasNext) {
+          if (gi + kLook < 16) kf[gi + kLook] = read_k(kn, gi + kLook);
+          else vf[gi + kLook - 16] = read_v(vc, gi + kLook - 16);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            sc_nxt[gi & 1][nt] =
+                __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[nt][gi >> 1], sc_nxt[gi & 1][nt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
           const int mt = gi >> 3, r = 2 * (gi & 7);
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][r], scale_log2, -m_use));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][r + 1], scale_log2, -m_use));
-          rs0 += p0;
-          rs1 += p1;
-          pk[mt][gi & 7] = pack_bf16(p0, p1);
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][nt][r], scale_log2, -m_use[nt]));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][nt][r + 1], scale_log2, -m_use[nt]));
+          pk[nt][mt][gi & 7] = pack_bf16(p0, p1);
+          // row sum of the rounded probabilities (what the second contraction multiplies with)
+#ifdef SHPLB_EXP_NO_DOT2
+          rs0[nt] += p0;
+          rs1[nt] += p1;
+#else
+          if (gi & 1) rs1[nt] = dot2_ones(pk[nt][mt][gi & 7], rs1[nt]);
+          else rs0[nt] = dot2_ones(pk[nt][mt][gi & 7], rs0[nt]);
+#endif
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      l_run += rs0 + rs1;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) l_run[nt] += rs0[nt] + rs1[nt];
 
-      // ---- O^T += V(t)^T P(t)^T
+      if (kHasNext) {
+        if (jv == i) mask_scores(sc_nxt, t + 1);
+      }
+
+      // ---- O^T += V(t)^T P(t)^T, with the row maxima of S(t+1) in between
+      float mx[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
 #pragma unroll
       for (int gi = 0; gi < 16; ++gi) {
         if (gi + kLook < 16) vf[gi + kLook] = read_v(vc, gi + kLook);
         const int gq = gi >> 2, dt = gi & 3;
-        const u32x4 w = {pk[gq >> 1][4 * (gq & 1)], pk[gq >> 1][4 * (gq & 1) + 1],
-                         pk[gq >> 1][4 * (gq & 1) + 2], pk[gq >> 1][4 * (gq & 1) + 3]};
-        acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[gi], __builtin_bit_cast(bf16x8, w), acc_o[dt], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const u32x4 w = {pk[nt][gq >> 1][4 * (gq & 1)], pk[nt][gq >> 1][4 * (gq & 1) + 1],
+                           pk[nt][gq >> 1][4 * (gq & 1) + 2], pk[nt][gq >> 1][4 * (gq & 1) + 3]};
+          acc_o[dt][nt] =
+              __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[gi], __builtin_bit_cast(bf16x8, w), acc_o[dt][nt], 0, 0, 0);
+          if (kHasNext) mx[nt] = fmaxf(mx[nt], fmaxf(sc_nxt[0][nt][gi], sc_nxt[1][nt][gi]));
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
+      if (kHasNext) settle_max(mx);
+    };
 
-      if (has_next) finish_scores(sc_nxt, t + 1);
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) sc_cur[mt] = sc_nxt[mt];
+    for (int b = 0; b + 1 < n_sel; ++b) {
+      const int j2 = block_of(b + 2);
+      step(std::true_type{}, sc_a, sc_b, 2 * b, j0, j1);
+      step(std::true_type{}, sc_b, sc_a, 2 * b + 1, j1, j1);
+      j0 = j1;
+      j1 = j2;
     }
+    step(std::true_type{}, sc_a, sc_b, n_tiles - 2, j0, j0);
+    step(std::false_type{}, sc_b, sc_a, n_tiles - 1, j0, j0);
 
     // ---- normalise and store: lane holds, for its query, dims 32dt + 8(r/4) + 4hi + (r%4)
-    {
-      const float l_tot = l_run + __shfl_xor(l_run, 32);
-      if (q_tok < seq_end) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+#ifdef SHPLB_EXP_NO_PAIRSUM
+      const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
+#else
+      const float l_tot = pair_sum(l_run[nt]);
+#endif
+      if (q_tok[nt] < seq_end) {
         const float inv = 1.0f / l_tot;
-        uint16_t* dst = out + int64_t(q_tok) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
+        uint16_t* dst = out + int64_t(q_tok[nt]) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
             u32x2 w;
-            w.x = pack_bf16(acc_o[dt][4 * rq] * inv, acc_o[dt][4 * rq + 1] * inv);
-            w.y = pack_bf16(acc_o[dt][4 * rq + 2] * inv, acc_o[dt][4 * rq + 3] * inv);
+            w.x = pack_bf16(acc_o[dt][nt][4 * rq] * inv, acc_o[dt][nt][4 * rq + 1] * inv);
+            w.y = pack_bf16(acc_o[dt][nt][4 * rq + 2] * inv, acc_o[dt][nt][4 * rq + 3] * inv);
             *reinterpret_cast<u32x2*>(dst + 32 * dt + 8 * rq) = w;
           }
         if (lse != nullptr && hi == 0)
-          lse[int64_t(h) * total_tokens + q_tok] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+          lse[int64_t(h) * total_tokens + q_tok[nt]] =
+              (m_ref[nt] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
       }
     }
     t_last = wall_clock64();
@@ -278,6 +380,10 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   }
 }
 
+#ifndef SHPLB_PIPE_NT
+#define SHPLB_PIPE_NT 1
+#endif
+
 }  // namespace
 
 void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
@@ -285,8 +391,8 @@ void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, c
                               shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
                               int32_t n_wg, hipStream_t stream) {
   const float scale_log2 = g.scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(attn_pipe_kernel, dim3(n_wg), dim3(256), 0, stream, g.meta, g.st,
-                     static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+  hipLaunchKernelGGL((attn_pipe_kernel<SHPLB_PIPE_NT>), dim3(n_wg), dim3(256 / SHPLB_PIPE_NT), 0, stream,
+                     g.meta, g.st, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                      static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
                      stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
 }

@@ -7,7 +7,7 @@ SCORE_ATOL = 2e-5      # fp32 pooling + fp32 dot of 128 terms against the fp64 o
 SEL_WAIVER = 1e-5      # a swap is allowed only between scores this close to the row's threshold
 OUT_MAX_ABS = 2e-2     # bf16 inputs, bf16 P, fp32 accumulate
 OUT_MAX_REL = 1e-2     # max|diff| / max|oracle| per head
-LSE_ATOL = 2e-3
+LSE_ATOL = 4e-3        # l sums the bf16-rounded probabilities: relative error up to 2^-9, plus fp32 exp/log
 
 
 def compare_selection(ptr, idx_gpu, idx_orc, scores_orc_rows, row_meta):
