@@ -43,7 +43,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   constexpr int QW = 32 * NT;                        // query rows per wave
   constexpr int kRoundRows = 4 * kWaves;             // rows one round of copies moves (4 per wave)
   constexpr int kRounds = kKeysPerTile / kRoundRows;
-  constexpr int kLook = NT == 1 ? 6 : 8;             // LDS operand fetches run this many groups ahead
+  constexpr int kLook = 8;             // LDS operand fetches run this many groups ahead
 
   __shared__ __attribute__((aligned(1024))) char k_lds[2][kTileBytes];
   __shared__ __attribute__((aligned(1024))) char v_lds[2][kTileBytes];
