@@ -64,11 +64,14 @@ WorkspaceLayout make_layout(const Geometry& g) {
   int64_t off = 0;
   w.qbar = off; off += align256(int64_t(g.meta.n_q_heads) * g.total_blocks * kHeadDim * 4);
   w.kbar = off; off += align256(int64_t(g.meta.n_kv_heads) * g.total_blocks * kHeadDim * 4);
+  w.order_by_cost = off; off += align256(g.rows * 4);
   w.order = off; off += align256(g.rows * 4);
   const int64_t n_chunks = (g.rows + kOrderChunk - 1) / kOrderChunk;
   w.hist = off; off += align256(n_chunks * kCostBins * 4);
   w.bin_start = off; off += align256(int64_t(kCostBins) * 4);
-  w.ticket = off; off += 256;
+  w.xcd_hist = off; off += align256(n_chunks * kXcds * 4);
+  w.queue_begin = off; off += 256;
+  w.tickets = off; off += align256(int64_t(kXcds) * kTicketStride * 4);
   w.total = off;
   return w;
 }
@@ -190,10 +193,11 @@ int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* q, const v
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (int32_t rc = launch_order(g, sel_ptr, w, ws, st)) return rc;
+  const WorkQueues wq{reinterpret_cast<const int32_t*>(ws + w.order),
+                      reinterpret_cast<const int32_t*>(ws + w.queue_begin),
+                      reinterpret_cast<uint32_t*>(ws + w.tickets)};
   return launch_attention(g, q, k, v, sel_ptr, sel_idx, out, lse_out,
-                          static_cast<shplb_wg_stats*>(sched_stats_out),
-                          reinterpret_cast<const int32_t*>(ws + w.order),
-                          reinterpret_cast<uint32_t*>(ws + w.ticket), n_wg, st);
+                          static_cast<shplb_wg_stats*>(sched_stats_out), wq, n_wg, st);
 }
 
 // Greedy multiway partition of Section 3.3.  n is a head (or KV-group) count, so

@@ -35,8 +35,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                       const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                       const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
                       uint16_t* __restrict__ out, float* __restrict__ lse,
-                      shplb_wg_stats* __restrict__ stats, const int32_t* __restrict__ order,
-                      uint32_t* __restrict__ ticket, int32_t rows, int64_t total_tokens,
+                      shplb_wg_stats* __restrict__ stats, WorkQueues wq, int64_t total_tokens,
                       float scale_log2) {
   constexpr int BQ = 128;
   constexpr int kWaves = 4 / NT;
@@ -75,14 +74,14 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 
   uint32_t my_items = 0, my_cost = 0;
   uint64_t t_first = 0, t_last = 0;
+  int queue = my_xcd(), exhausted = 0;   // work queue this workgroup currently draws from (thread 0 only)
 
   for (;;) {
-    if (tid == 0) s_item = int32_t(atomicAdd(ticket, 1u));
+    if (tid == 0) s_item = next_item(wq, queue, exhausted);
     __syncthreads();
-    const int item = __builtin_amdgcn_readfirstlane(s_item);
+    const int row = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
     __syncthreads();
-    if (item >= rows) break;
-    const int row = order[item];
+    if (row < 0) break;
     int s, h, i, nb;
     decode_row(meta, row, s, h, i, nb);
     const int g = h / group;
@@ -370,7 +369,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 
   if (stats != nullptr && tid == 0) {
     shplb_wg_stats rec;
-    rec.xcc_id = __builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20) & 0xf;       // XCC_ID[3:0]
+    rec.xcc_id = uint32_t(my_xcd());
     rec.cu_id = (__builtin_amdgcn_s_getreg((16 - 1) << 11 | 0 << 6 | 4) >> 8) & 0xff; // HW_ID[15:8]
     rec.n_items = my_items;
     rec.cost_blocks = my_cost;
@@ -388,13 +387,12 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 
 void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
                               const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                              shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
-                              int32_t n_wg, hipStream_t stream) {
+                              shplb_wg_stats* stats, WorkQueues wq, int32_t n_wg, hipStream_t stream) {
   const float scale_log2 = g.scale * 1.4426950408889634f;
   hipLaunchKernelGGL((attn_pipe_kernel<SHPLB_PIPE_NT>), dim3(n_wg), dim3(256 / SHPLB_PIPE_NT), 0, stream,
                      g.meta, g.st, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                      static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
-                     stats, order, ticket, int32_t(g.rows), g.total_tokens, scale_log2);
+                     stats, wq, g.total_tokens, scale_log2);
 }
 
 }  // namespace shplb

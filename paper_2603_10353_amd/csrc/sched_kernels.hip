@@ -1,12 +1,19 @@
-// Work-item ordering for the persistent attention launch: a stable counting sort of
-// the (sequence, head, query block) rows by descending selected-block count.
+// Work-item ordering for the persistent attention launch.
 //
-// The paper's greedy (Section 3.3) sorts units by descending cost and hands each to
-// the least-loaded worker.  On one GPU the workers are compute units: the sorted
-// list built here is consumed through a single atomic ticket, so the next-largest
-// item always goes to whichever workgroup becomes free first.
-// Equal costs keep their row order (head-major, then query block), which keeps
-// items that stream the same K/V blocks next to each other in time.
+// The paper's greedy (Section 3.3) sorts units by descending cost and hands each to the
+// least-loaded worker.  On one GPU the workers are compute units: the rows (sequence,
+// head, query block) are sorted by descending selected-block count and consumed through
+// atomic tickets, so the next-largest item always goes to a workgroup that just became
+// free.  MI355X has eight dies (XCDs), each with its own L2, so the sorted list is split
+// into one queue per die: all rows that stream one KV head of one sequence share a home
+// die, whose L2 then sees that K/V once.  A workgroup drains its die's queue first and
+// then helps the next die (see next_item()), which keeps the greedy's balance.
+//
+// Two stable counting sorts, least significant key first:
+//   1. by descending cost (per-256-row histograms, one-workgroup scan, scatter);
+//   2. by home die (8 bins; its histogram is accumulated by the first scatter).
+// Equal keys keep their row order (head-major, then query block), so items that stream
+// the same K/V blocks sit next to each other in a queue.  Everything is deterministic.
 #include "shplb_internal.h"
 
 namespace shplb {
@@ -17,11 +24,14 @@ __device__ __forceinline__ int cost_bin(const int64_t* sel_ptr, int row) {
   return int(c < 0 ? 0 : (c > kCostBins - 1 ? kCostBins - 1 : c));
 }
 
-// Pass 1: per-chunk histogram of costs.  hist[chunk][bin].
+// Sort 1, pass 1: per-chunk histogram of costs, hist[chunk][bin]; also clears the die
+// histogram of the chunk for sort 2.
 __global__ __launch_bounds__(kOrderChunk) void order_hist_kernel(
-    const int64_t* __restrict__ sel_ptr, int32_t* __restrict__ hist, int rows, int n_bins) {
+    const int64_t* __restrict__ sel_ptr, int32_t* __restrict__ hist, int32_t* __restrict__ xcd_hist,
+    int rows, int n_bins) {
   __shared__ int32_t h[kCostBins];
   for (int b = threadIdx.x; b < n_bins; b += kOrderChunk) h[b] = 0;
+  if (threadIdx.x < kXcds) xcd_hist[blockIdx.x * kXcds + threadIdx.x] = 0;
   __syncthreads();
   const int row = blockIdx.x * kOrderChunk + threadIdx.x;
   if (row < rows) atomicAdd(&h[min(cost_bin(sel_ptr, row), n_bins - 1)], 1);
@@ -30,12 +40,11 @@ __global__ __launch_bounds__(kOrderChunk) void order_hist_kernel(
   for (int b = threadIdx.x; b < n_bins; b += kOrderChunk) dst[b] = h[b];
 }
 
-// Pass 2 (one workgroup): turn hist[chunk][bin] into the exclusive count of earlier
-// chunks within the bin, and bin_start[bin] into the number of rows in costlier
-// bins.  Also resets the ticket the attention kernel draws from.
+// Sort 1, pass 2 (one workgroup): turn hist[chunk][bin] into the exclusive count of
+// earlier chunks within the bin, and bin_start[bin] into the number of rows in costlier
+// bins.
 __global__ __launch_bounds__(1024) void order_scan_kernel(
-    int32_t* __restrict__ hist, int32_t* __restrict__ bin_start, uint32_t* __restrict__ ticket,
-    int n_chunks, int n_bins) {
+    int32_t* __restrict__ hist, int32_t* __restrict__ bin_start, int n_chunks, int n_bins) {
   __shared__ int32_t total[kCostBins];
   __shared__ int32_t wave_sum[16];
   for (int b = threadIdx.x; b < n_bins; b += 1024) {
@@ -74,14 +83,15 @@ __global__ __launch_bounds__(1024) void order_scan_kernel(
     carry += all;
     __syncthreads();
   }
-  if (threadIdx.x == 0) ticket[0] = 0;
 }
 
-// Pass 3: scatter.  Position = rows in costlier bins + rows of the same bin in
-// earlier chunks + rows of the same bin earlier in this chunk.
+// Sort 1, pass 3: scatter.  Position = rows in costlier bins + rows of the same bin in
+// earlier chunks + rows of the same bin earlier in this chunk.  Counts the row into the
+// die histogram of the chunk its position falls in (sort 2, pass 1).
 __global__ __launch_bounds__(kOrderChunk) void order_scatter_kernel(
-    const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ hist,
-    const int32_t* __restrict__ bin_start, int32_t* __restrict__ order, int rows, int n_bins) {
+    SeqMeta meta, const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ hist,
+    const int32_t* __restrict__ bin_start, int32_t* __restrict__ order_by_cost,
+    int32_t* __restrict__ xcd_hist, int rows, int n_bins) {
   __shared__ int32_t bins[kOrderChunk];
   const int row = blockIdx.x * kOrderChunk + threadIdx.x;
   const int bin = row < rows ? min(cost_bin(sel_ptr, row), n_bins - 1) : -1;
@@ -90,7 +100,60 @@ __global__ __launch_bounds__(kOrderChunk) void order_scatter_kernel(
   if (row >= rows) return;
   int rank = 0;
   for (int x = 0; x < int(threadIdx.x); ++x) rank += bins[x] == bin;
-  order[bin_start[bin] + hist[int64_t(blockIdx.x) * n_bins + bin] + rank] = row;
+  const int pos = bin_start[bin] + hist[int64_t(blockIdx.x) * n_bins + bin] + rank;
+  order_by_cost[pos] = row;
+  atomicAdd(&xcd_hist[(pos / kOrderChunk) * kXcds + xcd_of_row(meta, row)], 1);
+}
+
+// Sort 2, pass 2 (one workgroup of 8 waves, wave x scans die x): exclusive prefix of the
+// die histogram over chunks, queue boundaries, and fresh tickets.
+__global__ __launch_bounds__(64 * kXcds) void queue_scan_kernel(
+    int32_t* __restrict__ xcd_hist, int32_t* __restrict__ queue_begin, uint32_t* __restrict__ tickets,
+    int n_chunks) {
+  __shared__ int32_t total[kXcds];
+  const int x = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int32_t carry = 0;
+  for (int base = 0; base < n_chunks; base += 64) {
+    const int c = base + lane;
+    const int32_t v = c < n_chunks ? xcd_hist[c * kXcds + x] : 0;
+    int32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int32_t up = __shfl_up(inc, d);
+      if (lane >= d) inc += up;
+    }
+    if (c < n_chunks) xcd_hist[c * kXcds + x] = carry + inc - v;
+    carry += __shfl(inc, 63);
+  }
+  if (lane == 0) {
+    total[x] = carry;
+    tickets[x * kTicketStride] = 0;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int32_t run = 0;
+    for (int d = 0; d < kXcds; ++d) {
+      queue_begin[d] = run;
+      run += total[d];
+    }
+    queue_begin[kXcds] = run;
+  }
+}
+
+// Sort 2, pass 3: scatter the cost-sorted rows into their die's queue.
+__global__ __launch_bounds__(kOrderChunk) void queue_scatter_kernel(
+    SeqMeta meta, const int32_t* __restrict__ order_by_cost, const int32_t* __restrict__ xcd_hist,
+    const int32_t* __restrict__ queue_begin, int32_t* __restrict__ order, int rows) {
+  __shared__ int32_t die[kOrderChunk];
+  const int pos = blockIdx.x * kOrderChunk + threadIdx.x;
+  const int row = pos < rows ? order_by_cost[pos] : -1;
+  const int x = row >= 0 ? xcd_of_row(meta, row) : -1;
+  die[threadIdx.x] = x;
+  __syncthreads();
+  if (row < 0) return;
+  int rank = 0;
+  for (int t = 0; t < int(threadIdx.x); ++t) rank += die[t] == x;
+  order[queue_begin[x] + xcd_hist[blockIdx.x * kXcds + x] + rank] = row;
 }
 
 }  // namespace
@@ -102,12 +165,20 @@ int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceL
   const int n_bins = min(g.max_nb + 1, kCostBins);
   int32_t* hist = reinterpret_cast<int32_t*>(workspace + w.hist);
   int32_t* bin_start = reinterpret_cast<int32_t*>(workspace + w.bin_start);
+  int32_t* order_by_cost = reinterpret_cast<int32_t*>(workspace + w.order_by_cost);
   int32_t* order = reinterpret_cast<int32_t*>(workspace + w.order);
-  uint32_t* ticket = reinterpret_cast<uint32_t*>(workspace + w.ticket);
-  hipLaunchKernelGGL(order_hist_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, sel_ptr, hist, rows, n_bins);
-  hipLaunchKernelGGL(order_scan_kernel, dim3(1), dim3(1024), 0, stream, hist, bin_start, ticket, n_chunks, n_bins);
-  hipLaunchKernelGGL(order_scatter_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, sel_ptr, hist,
-                     bin_start, order, rows, n_bins);
+  int32_t* xcd_hist = reinterpret_cast<int32_t*>(workspace + w.xcd_hist);
+  int32_t* queue_begin = reinterpret_cast<int32_t*>(workspace + w.queue_begin);
+  uint32_t* tickets = reinterpret_cast<uint32_t*>(workspace + w.tickets);
+  hipLaunchKernelGGL(order_hist_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, sel_ptr, hist, xcd_hist,
+                     rows, n_bins);
+  hipLaunchKernelGGL(order_scan_kernel, dim3(1), dim3(1024), 0, stream, hist, bin_start, n_chunks, n_bins);
+  hipLaunchKernelGGL(order_scatter_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, g.meta, sel_ptr, hist,
+                     bin_start, order_by_cost, xcd_hist, rows, n_bins);
+  hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(64 * kXcds), 0, stream, xcd_hist, queue_begin, tickets,
+                     n_chunks);
+  hipLaunchKernelGGL(queue_scatter_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, g.meta, order_by_cost,
+                     xcd_hist, queue_begin, order, rows);
   if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
   return SHPLB_OK;
 }

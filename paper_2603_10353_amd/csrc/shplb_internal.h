@@ -10,6 +10,8 @@ namespace shplb {
 constexpr int kHeadDim = 128;
 constexpr int kCostBins = 4100;       // selected-block counts 0..SHPLB_MAX_BLOCKS, rounded up
 constexpr int kOrderChunk = 256;      // rows per workgroup in the ordering kernels
+constexpr int kXcds = 8;              // accelerator dies (XCDs) of an MI355X, each with its own L2
+constexpr int kTicketStride = 16;     // uint32 slots between two queue tickets (one 64-byte line each)
 
 // Sequence geometry, passed to kernels by value (about 1 KB of kernel arguments).
 struct SeqMeta {
@@ -40,10 +42,13 @@ struct Geometry {
 // Workspace carve-up (byte offsets, each 256-byte aligned).
 struct WorkspaceLayout {
   int64_t qbar, kbar;        // fp32 [H][total_blocks][128]
-  int64_t order;             // int32 [rows]
+  int64_t order_by_cost;     // int32 [rows]: rows by descending cost (intermediate)
+  int64_t order;             // int32 [rows]: the same, split into one queue per XCD
   int64_t hist;              // int32 [n_chunks][kCostBins]
   int64_t bin_start;         // int32 [kCostBins]
-  int64_t ticket;            // uint32 [64] (one used; padded to its own cache lines)
+  int64_t xcd_hist;          // int32 [n_chunks][kXcds]
+  int64_t queue_begin;       // int32 [kXcds + 1]: queue x is order[queue_begin[x] .. queue_begin[x+1])
+  int64_t tickets;           // uint32 [kXcds * kTicketStride]
   int64_t total;
 };
 
@@ -58,16 +63,21 @@ int32_t launch_select(const Geometry& g, const float* scores, const int64_t* sel
                       int32_t* sel_idx, hipStream_t stream);
 int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceLayout& w,
                      char* workspace, hipStream_t stream);
+// The per-XCD work queues the ordering kernels build (device pointers into the workspace).
+struct WorkQueues {
+  const int32_t* order;        // rows, queue after queue, each by descending cost
+  const int32_t* queue_begin;  // [kXcds + 1]
+  uint32_t* tickets;           // [kXcds * kTicketStride], zeroed by the ordering kernels
+};
+
 int32_t launch_attention(const Geometry& g, const void* q, const void* k, const void* v,
                          const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                         shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
-                         int32_t n_wg, hipStream_t stream);
+                         shplb_wg_stats* stats, WorkQueues wq, int32_t n_wg, hipStream_t stream);
 
 // Pipelined variant for 128-token blocks (attn_pipe_kernel.hip).
 void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
                               const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                              shplb_wg_stats* stats, const int32_t* order, uint32_t* ticket,
-                              int32_t n_wg, hipStream_t stream);
+                              shplb_wg_stats* stats, WorkQueues wq, int32_t n_wg, hipStream_t stream);
 
 // Row -> (sequence, head, query block).  Rows of one sequence are contiguous.
 __device__ __forceinline__ void decode_row(const SeqMeta& m, int32_t row, int& s, int& h, int& i, int& nb) {
@@ -77,6 +87,37 @@ __device__ __forceinline__ void decode_row(const SeqMeta& m, int32_t row, int& s
   nb = m.blk_begin[s + 1] - m.blk_begin[s];
   h = local / nb;
   i = local - h * nb;
+}
+
+// Home XCD of a row.  All rows that stream the same K/V (one KV head of one sequence) go to
+// the same die, so its L2 sees one K/V stream per resident head instead of all of them;
+// with fewer streams than dies a stream is spread over several dies by query block.
+__device__ __forceinline__ int xcd_of_row(const SeqMeta& m, int32_t row) {
+  int s, h, i, nb;
+  decode_row(m, row, s, h, i, nb);
+  const int stream = s * m.n_kv_heads + h / (m.n_q_heads / m.n_kv_heads);
+  const int n_streams = m.n_seq * m.n_kv_heads;
+  if (n_streams >= kXcds) return stream % kXcds;
+  const int per = kXcds / n_streams;
+  return stream * per + i % per;
+}
+
+// Next work item for a persistent workgroup (called by one thread): take from the current
+// queue (first the home XCD's), move on to the next die's queue when it is exhausted.
+// Returns the row, or -1 when every queue is empty.
+__device__ __forceinline__ int32_t next_item(const WorkQueues& wq, int& queue, int& exhausted) {
+  while (exhausted < kXcds) {
+    const int begin = wq.queue_begin[queue], end = wq.queue_begin[queue + 1];
+    const uint32_t t = atomicAdd(wq.tickets + queue * kTicketStride, 1u);
+    if (t < uint32_t(end - begin)) return wq.order[begin + int(t)];
+    queue = (queue + 1) % kXcds;
+    ++exhausted;
+  }
+  return -1;
+}
+
+__device__ __forceinline__ int my_xcd() {
+  return int(__builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20) & 0xf) % kXcds;   // XCC_ID[3:0]
 }
 
 }  // namespace shplb
