@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM traffic of one attention launch measured with rocprofv3 --pmc (FETCH_SIZE, then
 # WRITE_SIZE), scaled by a copy kernel of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg2_llama3_8b_128k": 2 * 23702939.2 * 1024 + 1075872.5 * 1024}
+MEASURED_TRAFFIC_BYTES = {"cfg2_llama3_8b_128k": 2 * 15285813.6 * 1024 + 1142255.7 * 1024}
 
 
 def selected_pairs(cu_seqlens, block, n_q_heads, sel_ptr_host):
@@ -229,7 +229,7 @@ def main():
                          "idle_fraction_of_span": idle_frac, "workgroups": int(len(st))},
         "roofline": {"bound": "mfma", "achieved": attn_tflops, "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": attn_tflops / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "kernel": "attn_kernel",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "kernel": "attn_pipe_kernel" if wl.block == 128 else "attn_kernel",
                      "kernel_ms": attn_ms},
         "host_input_generation_s": t_gen,
     }

@@ -85,7 +85,7 @@ int32_t persistent_workgroups() {
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
       return SHPLB_E_HIP;
-    cached[dev] = cus * 2;   // two 128-thread workgroups per compute unit (one wave per SIMD)
+    cached[dev] = cus * 2;   // two workgroups per compute unit (two waves per SIMD)
   }
   return cached[dev];
 }

@@ -3,10 +3,11 @@
 // Same data layout as attn_kernel.hip (64-key tiles, S^T = K Q^T then O^T += V^T P^T,
 // swizzled 256-byte LDS rows filled by direct global->LDS copies).  What differs:
 //
-//   * a wave owns 32*NT query rows.  With NT = 2 a 128-row query block is two waves of
-//     64 rows, every K / V operand fetched from LDS feeds two MFMAs (half the LDS read
-//     traffic of the 32-row layout), and a wave may use the full 512-entry register
-//     file (one wave per SIMD, two workgroups per compute unit);
+//   * a wave owns 32*NT query rows.  The library builds NT = 1: four waves of 32 rows, two
+//     workgroups per compute unit, so each SIMD holds two waves of different workgroups
+//     and a wave has 256 registers.  NT = 2 (64 rows per wave, every LDS operand feeding
+//     two MFMAs, one 512-register wave per SIMD) compiles, but the compiler cannot keep
+//     its accumulators in place and moves hundreds of them per tile: it is not used;
 //   * the order of work inside a wave: the contraction S(t+1) = K(t+1) Q^T is issued
 //     while the exponentials of tile t run, and the row maxima of S(t+1) are taken
 //     between the MFMAs of O += V(t)^T P(t)^T, so the softmax VALU work executes under
