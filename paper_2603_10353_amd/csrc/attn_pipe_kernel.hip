@@ -8,17 +8,19 @@
 //     and a wave has 256 registers.  NT = 2 (64 rows per wave, every LDS operand feeding
 //     two MFMAs, one 512-register wave per SIMD) compiles, but the compiler cannot keep
 //     its accumulators in place and moves hundreds of them per tile: it is not used;
-//   * the order of work inside a wave: the contraction S(t+1) = K(t+1) Q^T is issued
-//     while the exponentials of tile t run, and the row maxima of S(t+1) are taken
-//     between the MFMAs of O += V(t)^T P(t)^T, so the softmax VALU work executes under
-//     the wave's own MFMAs:
+//   * the order of work inside a wave.  A step handles tile t's softmax and second
+//     contraction and tile t+1's first contraction:
 //
 //       step t:  barrier                      K(t+1), V(t) resident; stages of K(t), V(t-1) free
 //                copies K(t+2), V(t+1) start
-//                16 x { NT MFMAs of S(t+1) ; exp / sum / bf16 pack of 2*NT probabilities of tile t }
-//                mask S(t+1) if it is the diagonal block
-//                16 x { NT MFMAs of O += V(t)^T P(t)^T ; one step of the row maxima of S(t+1) }
+//                16 MFMAs of S(t+1), back to back; mask S(t+1) if it is the diagonal block
+//                exp / bf16 pack / row sum of the 32 probabilities of tile t (one run of VALU work)
+//                16 x { MFMA of O += V(t)^T P(t)^T ; one step of the row maxima of S(t+1) }
 //                raise the running maximum if some row grew by more than 2^8 (rare)
+//
+//     so a wave alternates between blocks of MFMAs and a block of VALU work that depends
+//     on none of the MFMAs in flight, and the two waves of a SIMD (of different workgroups,
+//     unsynchronised) mostly find the other unit free;
 //
 // The two score buffers swap roles from step to step (the tile count is even, steps are
 // issued in pairs).  LDS operands are fetched kLook groups ahead of their use.  Fully
@@ -174,11 +176,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       bool grow = false;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-#ifdef SHPLB_EXP_SHFL_MAX
-        mx[nt] = fmaxf(mx[nt], __shfl_xor(mx[nt], 32)) * scale_log2;
-#else
         mx[nt] = pair_max(mx[nt]) * scale_log2;
-#endif
         grow = grow || (mx[nt] > m_ref[nt] + kRescaleSlack);
       }
       if (__any(grow)) {
@@ -266,7 +264,8 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
             for (int r = 0; r < 16; ++r) sc_nxt[mt][nt][r] = 0.0f;
       }
 
-      // ---- S(t+1) under the exponentials of tile t
+      // ---- S(t+1): sixteen MFMAs back to back (the operands of the second contraction are
+      // fetched behind the last K operands)
       if (kHasNext) {
 #pragma unroll
         for (int gi = 0; gi < kLook; ++gi) kf[gi] = read_k(kn, gi);
@@ -275,39 +274,39 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
         for (int gi = 0; gi < kLook; ++gi) vf[gi] = read_v(vc, gi);
       }
       __builtin_amdgcn_sched_barrier(0);
+      if (kHasNext) {
 #pragma unroll
-      for (int gi = 0; gi < 16; ++gi) {
-        if (kHasNext) {
+        for (int gi = 0; gi < 16; ++gi) {
           if (gi + kLook < 16) kf[gi + kLook] = read_k(kn, gi + kLook);
           else vf[gi + kLook - 16] = read_v(vc, gi + kLook - 16);
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
             sc_nxt[gi & 1][nt] =
                 __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[nt][gi >> 1], sc_nxt[gi & 1][nt], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
+        if (jv == i) mask_scores(sc_nxt, t + 1);
+      }
+
+      // ---- probabilities of tile t, in one run of VALU work: the S(t+1) MFMAs of this wave
+      // are still in flight and the other wave of the SIMD is usually inside an MFMA block.
+      // (Spread between the MFMAs above, the same instructions make the kernel 2-4% slower.)
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-          const int mt = gi >> 3, r = 2 * (gi & 7);
+          const int mt = u >> 3, r = 2 * (u & 7);
           const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][nt][r], scale_log2, -m_use[nt]));
           const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][nt][r + 1], scale_log2, -m_use[nt]));
-          pk[nt][mt][gi & 7] = pack_bf16(p0, p1);
+          pk[nt][mt][u & 7] = pack_bf16(p0, p1);
           // row sum of the rounded probabilities (what the second contraction multiplies with)
-#ifdef SHPLB_EXP_NO_DOT2
-          rs0[nt] += p0;
-          rs1[nt] += p1;
-#else
-          if (gi & 1) rs1[nt] = dot2_ones(pk[nt][mt][gi & 7], rs1[nt]);
-          else rs0[nt] = dot2_ones(pk[nt][mt][gi & 7], rs0[nt]);
-#endif
+          if (u & 1) rs1[nt] = dot2_ones(pk[nt][mt][u & 7], rs1[nt]);
+          else rs0[nt] = dot2_ones(pk[nt][mt][u & 7], rs0[nt]);
         }
-        __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) l_run[nt] += rs0[nt] + rs1[nt];
-
-      if (kHasNext) {
-        if (jv == i) mask_scores(sc_nxt, t + 1);
-      }
+      __builtin_amdgcn_sched_barrier(0);
 
       // ---- O^T += V(t)^T P(t)^T, with the row maxima of S(t+1) in between
       float mx[NT];
@@ -343,11 +342,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     // ---- normalise and store: lane holds, for its query, dims 32dt + 8(r/4) + 4hi + (r%4)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-#ifdef SHPLB_EXP_NO_PAIRSUM
-      const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
-#else
       const float l_tot = pair_sum(l_run[nt]);
-#endif
       if (q_tok[nt] < seq_end) {
         const float inv = 1.0f / l_tot;
         uint16_t* dst = out + int64_t(q_tok[nt]) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
