@@ -62,8 +62,8 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g) {
 WorkspaceLayout make_layout(const Geometry& g) {
   WorkspaceLayout w;
   int64_t off = 0;
-  w.qbar = off; off += align256(int64_t(g.meta.n_q_heads) * g.total_blocks * kHeadDim * 4);
-  w.kbar = off; off += align256(int64_t(g.meta.n_kv_heads) * g.total_blocks * kHeadDim * 4);
+  w.qbar = off; off += align256(int64_t(g.meta.n_q_heads) * g.total_blocks * kHeadDim * 6);
+  w.kbar = off; off += align256(int64_t(g.meta.n_kv_heads) * g.total_blocks * kHeadDim * 6);
   w.order_by_cost = off; off += align256(g.rows * 4);
   w.order = off; off += align256(g.rows * 4);
   const int64_t n_chunks = (g.rows + kOrderChunk - 1) / kOrderChunk;
@@ -161,8 +161,10 @@ int32_t shplb_block_scores(const shplb_problem* p, const void* q, const void* k,
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return SHPLB_E_SHAPE;
   const WorkspaceLayout w = make_layout(g);
   char* ws = static_cast<char*>(workspace);
-  return launch_pool_scores(g, q, k, scores_out, reinterpret_cast<float*>(ws + w.qbar),
-                            reinterpret_cast<float*>(ws + w.kbar), static_cast<hipStream_t>(stream));
+  const int32_t n_wg = persistent_workgroups();   // two per compute unit
+  if (n_wg < 0) return SHPLB_E_HIP;
+  return launch_pool_scores(g, q, k, scores_out, reinterpret_cast<uint16_t*>(ws + w.qbar),
+                            reinterpret_cast<uint16_t*>(ws + w.kbar), n_wg / 2, static_cast<hipStream_t>(stream));
 }
 
 int32_t shplb_select_topk_per_head(const shplb_problem* p, const float* scores,

@@ -41,7 +41,7 @@ struct Geometry {
 
 // Workspace carve-up (byte offsets, each 256-byte aligned).
 struct WorkspaceLayout {
-  int64_t qbar, kbar;        // fp32 [H][total_blocks][128]
+  int64_t qbar, kbar;        // pooled blocks as three bf16 planes, each [H][total_blocks][128]
   int64_t order_by_cost;     // int32 [rows]: rows by descending cost (intermediate)
   int64_t order;             // int32 [rows]: the same, split into one queue per XCD
   int64_t hist;              // int32 [n_chunks][kCostBins]
@@ -58,7 +58,7 @@ int32_t persistent_workgroups();   // for the current device; <0 on HIP error
 
 // Kernel launchers (each returns a SHPLB status).
 int32_t launch_pool_scores(const Geometry& g, const void* q, const void* k, float* scores,
-                           float* qbar, float* kbar, hipStream_t stream);
+                           uint16_t* q_planes, uint16_t* k_planes, int n_compute_units, hipStream_t stream);
 int32_t launch_select(const Geometry& g, const float* scores, const int64_t* sel_ptr,
                       int32_t* sel_idx, hipStream_t stream);
 int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceLayout& w,
