@@ -75,3 +75,20 @@ def test_config3_one_partition_share_64k():
 def test_config4_varlen_batch_quarter_scale():
     # the 8K+24K+64K+128K batch at a quarter of its lengths (ragged by one token each), one launch
     _run_case(make_workload(4, seqlens=[2048 + 1, 6144 - 1, 16384 + 63, 32768 - 65]), 48, seed=4)
+
+
+def test_max_blocks_per_sequence():
+    # 4096 blocks of 64 tokens: the largest block count the library accepts (wide selection kernel,
+    # score tiles in rounds, 64-token attention kernel at scale); the last block is ragged.
+    from workloads import make_custom
+    wl = make_custom([64 * 4096 - 37], 2, 1, 64, [48, 700], seed=77, name="max_blocks")
+    _run_case(wl, 12, seed=7)
+
+
+def test_max_sequences_per_call():
+    # 64 sequences (the most one call takes), lengths from one token to a few blocks, GQA 4:1.
+    from workloads import make_custom
+    rng = np.random.default_rng(64)
+    seqlens = [1, 127, 128, 129] + rng.integers(1, 900, size=60).tolist()
+    wl = make_custom(seqlens, 8, 2, 128, [1, 2, 3, 4, 6, 9, 2, 100], seed=78, name="max_seq")
+    _run_case(wl, 64, seed=8)
