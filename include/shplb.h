@@ -104,7 +104,9 @@ SHPLB_API int32_t shplb_sched_num_workgroups(const shplb_problem* p, int32_t* n_
 /* Block importance (the estimator the paper leaves to its borrowed kernels,
  * Section 4; scale from Eq. 1): mean-pool the valid tokens of every query block
  * and key block, then scores[s][h][i][j] = (Qbar[h,i] . Kbar[h/G,j]) * scale for
- * j <= i.  Entries with j > i are not written.  fp32 throughout.
+ * j <= i.  Entries with j > i are not written.  Means, products and sums carry
+ * fp32 precision (products are formed from exact three-way bf16 splits of the
+ * fp32 means and accumulated in fp32).
  *   q, k: device bf16.  scores_out: device fp32, shplb_score_layout() floats.
  *   workspace: device, shplb_workspace_bytes(). */
 SHPLB_API int32_t shplb_block_scores(const shplb_problem* p, const void* q, const void* k,
