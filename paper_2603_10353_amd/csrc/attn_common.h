@@ -16,6 +16,8 @@ constexpr int kKeysPerTile = 64;
 constexpr int kRowBytes = 256;                          // one key row (128 bf16) in LDS
 constexpr int kTileBytes = kKeysPerTile * kRowBytes;    // 16 KB per K or V tile
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row maximum may grow before O, l are rescaled
+constexpr float kRowSumLimit = 8192.0f; // = 32 * 2^slack: a lane's 32 probabilities of a tile can only sum
+                                        // to more if one of them exceeds 2^slack
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))

@@ -14,9 +14,10 @@
 //       step t:  barrier                      K(t+1), V(t) resident; stages of K(t), V(t-1) free
 //                copies K(t+2), V(t+1) start
 //                16 MFMAs of S(t+1), back to back; mask S(t+1) if it is the diagonal block
-//                exp / bf16 pack / row sum of the 32 probabilities of tile t (one run of VALU work)
-//                16 x { MFMA of O += V(t)^T P(t)^T ; one step of the row maxima of S(t+1) }
-//                raise the running maximum if some row grew by more than 2^8 (rare)
+//                exp / bf16 pack / row sum of the 32 probabilities of tile t (one run of VALU work);
+//                if a row sum shows that the reference maximum was too low (rare): true
+//                maximum of the tile, rescale O and l, probabilities again
+//                16 MFMAs of O += V(t)^T P(t)^T, back to back
 //
 //     so a wave alternates between blocks of MFMAs and a block of VALU work that depends
 //     on none of the MFMAs in flight, and the two waves of a SIMD (of different workgroups,
@@ -171,18 +172,12 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
           }
       }
     };
-    // mx[nt] = in-lane maximum of the tile's scores; raise the running maximum when needed
+    // mx[nt] = in-lane maximum of a tile's scores: raise the reference to it where it is higher
     auto settle_max = [&](float (&mx)[NT]) {
-      bool grow = false;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        mx[nt] = pair_max(mx[nt]) * scale_log2;
-        grow = grow || (mx[nt] > m_ref[nt] + kRescaleSlack);
-      }
-      if (__any(grow)) {
+      {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-          const float m_new = fmaxf(m_ref[nt], mx[nt]);
+          const float m_new = fmaxf(m_ref[nt], pair_max(mx[nt]) * scale_log2);
           const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
           m_ref[nt] = m_new;
           l_run[nt] *= alpha;
@@ -291,27 +286,52 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       // ---- probabilities of tile t, in one run of VALU work: the S(t+1) MFMAs of this wave
       // are still in flight and the other wave of the SIMD is usually inside an MFMA block.
       // (Spread between the MFMAs above, the same instructions make the kernel 2-4% slower.)
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
+      auto probabilities = [&]() {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-          const int mt = u >> 3, r = 2 * (u & 7);
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][nt][r], scale_log2, -m_use[nt]));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][nt][r + 1], scale_log2, -m_use[nt]));
-          pk[nt][mt][u & 7] = pack_bf16(p0, p1);
-          // row sum of the rounded probabilities (what the second contraction multiplies with)
-          if (u & 1) rs1[nt] = dot2_ones(pk[nt][mt][u & 7], rs1[nt]);
-          else rs0[nt] = dot2_ones(pk[nt][mt][u & 7], rs0[nt]);
+          m_use[nt] = m_ref[nt] == -INFINITY ? 0.0f : m_ref[nt];
+          rs0[nt] = rs1[nt] = 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const int mt = u >> 3, r = 2 * (u & 7);
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][nt][r], scale_log2, -m_use[nt]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc_cur[mt][nt][r + 1], scale_log2, -m_use[nt]));
+            pk[nt][mt][u & 7] = pack_bf16(p0, p1);
+            // row sum of the rounded probabilities (what the second contraction multiplies with)
+            if (u & 1) rs1[nt] = dot2_ones(pk[nt][mt][u & 7], rs1[nt]);
+            else rs0[nt] = dot2_ones(pk[nt][mt][u & 7], rs0[nt]);
+          }
+        }
+      };
+      probabilities();
+      // The reference m_ref was fixed by earlier tiles.  It is too low for this tile exactly
+      // when a probability came out large, and then the tile's row sum is large: no maximum
+      // over the scores is needed to notice.  In that (rare) case take the tile's true
+      // maximum, raise the reference, rescale O and l, and redo the tile's probabilities.
+      {
+        bool big = false;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) big = big || !(rs0[nt] + rs1[nt] <= kRowSumLimit);
+        if (__any(big)) {
+          float mx[NT];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            mx[nt] = fmaxf(sc_cur[0][nt][0], sc_cur[1][nt][0]);
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx[nt] = fmaxf(mx[nt], fmaxf(sc_cur[0][nt][r], sc_cur[1][nt][r]));
+          }
+          settle_max(mx);
+          probabilities();
         }
       }
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) l_run[nt] += rs0[nt] + rs1[nt];
       __builtin_amdgcn_sched_barrier(0);
 
-      // ---- O^T += V(t)^T P(t)^T, with the row maxima of S(t+1) in between
-      float mx[NT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) mx[nt] = -INFINITY;
+      // ---- O^T += V(t)^T P(t)^T: sixteen MFMAs back to back
 #pragma unroll
       for (int gi = 0; gi < 16; ++gi) {
         if (gi + kLook < 16) vf[gi + kLook] = read_v(vc, gi + kLook);
@@ -322,11 +342,9 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                            pk[nt][gq >> 1][4 * (gq & 1) + 2], pk[nt][gq >> 1][4 * (gq & 1) + 3]};
           acc_o[dt][nt] =
               __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[gi], __builtin_bit_cast(bf16x8, w), acc_o[dt][nt], 0, 0, 0);
-          if (kHasNext) mx[nt] = fmaxf(mx[nt], fmaxf(sc_nxt[0][nt][gi], sc_nxt[1][nt][gi]));
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (kHasNext) settle_max(mx);
     };
 
     for (int b = 0; b + 1 < n_sel; ++b) {
