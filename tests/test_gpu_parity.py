@@ -109,3 +109,21 @@ def test_deterministic_across_runs():
     run.run_all()
     assert torch.equal(run.out.view(torch.int16), o1.view(torch.int16))
     assert torch.equal(run.lse, l1) and torch.equal(run.sel_idx, i1)
+
+
+def test_rising_and_falling_scores():
+    # Keys whose logits climb by several nats from tile to tile (the running reference of the
+    # softmax is too low again and again: rescale path), then fall far below it (stale
+    # reference, probabilities near the bottom of the fp32 range).  Every block selected.
+    from workloads import bf16_bits_from_f32, f32_from_bf16_bits
+    wl = make_custom([128 * 14 + 50], 2, 1, 128, [15, 15], seed=91, name="rising")
+    q = f32_from_bf16_bits(wl.q)
+    k = f32_from_bf16_bits(wl.k)
+    u = q[:, 0, :].mean(axis=0)
+    u /= np.linalg.norm(u)
+    T = k.shape[0]
+    tile = np.arange(T) // 64
+    push = np.where(tile < 18, 9.0 * tile, 9.0 * 18 - 30.0 * (tile - 18))      # up 18 tiles, then steeply down
+    k[:, 0, :] += (push[:, None] * u[None, :]).astype(np.float32)
+    wl.k = bf16_bits_from_f32(k)
+    full_parity(wl)
