@@ -119,7 +119,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build covers one GPU's share of the path; run with --gpus 1 "
-                 "(heads shard across GPUs with no exchange, see DESIGN.md)")
+                 "(heads shard across GPUs with no exchange; nothing here needs a second GPU)")
 
     import torch
     import paper_2603_10353_amd as S
