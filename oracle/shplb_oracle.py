@@ -26,10 +26,22 @@ What the paper fixes and what it leaves open
     budget with the highest-scoring earlier blocks, ties to the lower index; the
     budget is per head, in blocks, and applies to every query-block row of the head.
 
+  * Budgets come from max-min budget shifting (Section 3.2): start from equal budgets
+    and move budget from the head with the highest recovery ratio to the head with the
+    lowest until the giver has become the minimum or nobody above the lower bound is
+    left to give.  The paper states neither the step nor the exact test; readings:
+    one step of `step` units per move; the receiver is the lowest-recovery head, the
+    giver the highest-recovery other head that can still give (ties to the lower
+    index); a move that would lower the minimum recovery is not made and ends the
+    iteration; a move that is made and leaves the giver as the (possibly tied)
+    minimum ends it too; an indivisible total gives its remainder to the first heads.
+
 Pins (tests/test_oracle_*.py): dense special case vs a textbook attention routine,
 row sums, constant-V, sink+diagonal special case, selection-order invariance,
 closed-form pooled scores, brute-force top-k, constructed ties, hand-worked greedy
-instance, exhaustive optimum on tiny partitions, cost closed form.
+instance, exhaustive optimum on tiny partitions, cost closed form; budget shifting:
+hand-worked instance, identical curves, exhaustive max-min optimum for two heads,
+invariants and the no-further-move property on random monotone curves.
 Parity unpinned: how well pooled-score selection tracks true attention mass (needs
 the paper's models and data); only self-consistency is checked.
 """
@@ -250,3 +262,47 @@ def imbalance(loads: Sequence[float]) -> float:
     """Eq. 2 objective: max load over mean load."""
     loads = [float(x) for x in loads]
     return max(loads) / (sum(loads) / len(loads))
+
+
+# --------------------------------------------------------------------------- budgets (Section 3.2)
+def shift_budgets(recovery: np.ndarray, total: int, lower: int, step: int = 1) -> Tuple[np.ndarray, int]:
+    """Max-min sparsity budget shifting (Section 3.2).
+
+    recovery[h][b]: attention-weight recovery ratio of head h under a budget of b units,
+    b = 0 .. n_levels-1, non-decreasing in b.  `total` units are shared out, no head
+    below `lower`.  Returns (budgets int64 [n_heads], number of moves made).
+
+    The steps, in the paper's order: equal budgets; repeatedly move `step` units from
+    the head with the highest recovery ratio (highest sparsity) to the head with the
+    lowest; stop when (i) the giver has become the new minimum, i.e. further moves
+    cannot help, or (ii) nobody above the lower bound is left to give.
+    """
+    rec = np.asarray(recovery, dtype=np.float64)
+    n_heads, n_levels = rec.shape
+    if n_heads < 1 or step < 1 or lower < 0:
+        raise ValueError("bad arguments")
+    if np.any(np.diff(rec, axis=1) < 0):
+        raise ValueError("recovery curves must be non-decreasing")
+    base, extra = divmod(int(total), n_heads)
+    b = [base + (1 if h < extra else 0) for h in range(n_heads)]        # equal budgets
+    if min(b) < lower or max(b) > n_levels - 1:
+        raise ValueError("total does not fit between the lower bound and the curves' range")
+    moves = 0
+    while True:
+        now = [rec[h][b[h]] for h in range(n_heads)]
+        recv = min(range(n_heads), key=lambda h: (now[h], h))           # lowest recovery, then lowest index
+        givers = [h for h in range(n_heads) if h != recv and b[h] - step >= lower]
+        if not givers or b[recv] + step > n_levels - 1:
+            break                                                       # (ii): nothing left to move
+        give = min(givers, key=lambda h: (-now[h], h))                  # highest recovery, then lowest index
+        after = list(now)
+        after[give] = rec[give][b[give] - step]
+        after[recv] = rec[recv][b[recv] + step]
+        if min(after) < min(now):
+            break                                                       # (i): the move would not help
+        b[give] -= step
+        b[recv] += step
+        moves += 1
+        if after[give] <= min(after):
+            break                                                       # (i): the giver is the new minimum
+    return np.asarray(b, dtype=np.int64), moves
