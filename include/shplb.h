@@ -9,6 +9,7 @@
  *   shplb_sparse_attn_prefill   block-sparse causal attention over the selection,
  *                               work items dealt to compute units by descending cost
  *   shplb_balance_heads         greedy head-to-partition assignment (host)
+ *   shplb_shift_budgets         max-min budget shifting: the producer of the budgets (host)
  *
  * Conventions
  *   - Every function returns an int32 status: 0 = OK, negative = error (see
@@ -156,6 +157,28 @@ SHPLB_API int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* 
  * (negative cost, or max_per_part * n_parts < n). */
 SHPLB_API int32_t shplb_balance_heads(const int64_t* costs, int32_t n, int32_t n_parts,
                             int32_t max_per_part, int32_t* part_of_out, int64_t* loads_out);
+
+/* Max-min sparsity budget shifting (Section 3.2): share `total` budget units
+ * among the heads so that the lowest attention-weight recovery ratio is as high
+ * as the iteration gets it.  Start from equal budgets (an indivisible total gives
+ * its remainder to the first heads); then repeatedly move `step` units from the
+ * head with the highest recovery ratio that can still give (budget - step >=
+ * lower; equal ratios: lowest index) to the head with the lowest ratio (equal:
+ * lowest index).  A move that would lower the minimum ratio is not made and ends
+ * the iteration; a move that leaves the giver as the (possibly tied) minimum is
+ * made and ends it; so does running out of givers or the receiver reaching the
+ * end of its curve.  The paper fixes neither the step nor these tests.
+ * All pointers are host memory.
+ *   recovery [n_heads][n_levels] row-major: recovery[h][b] = ratio of head h under
+ *     a budget of b units, b = 0 .. n_levels-1, non-decreasing in b.
+ *   budgets_out [n_heads] (units); n_moves_out: number of moves made, or NULL.
+ * The unit is the caller's (the device steps take budgets in key blocks).
+ * Errors: SHPLB_E_NULL; SHPLB_E_SHAPE (n_heads < 1, n_levels < 1, step < 1,
+ * lower < 0, a decreasing or non-finite curve); SHPLB_E_BUDGET (the equal start
+ * lies below `lower` or beyond the curves). */
+SHPLB_API int32_t shplb_shift_budgets(const double* recovery, int32_t n_heads, int32_t n_levels,
+                            int64_t total, int32_t lower, int32_t step,
+                            int32_t* budgets_out, int64_t* n_moves_out);
 
 SHPLB_API const char* shplb_strerror(int32_t status);
 

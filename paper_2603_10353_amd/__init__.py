@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     shplb_sched_num_workgroups,
     shplb_score_layout,
     shplb_sel_row_ptr,
+    shplb_shift_budgets,
     shplb_select_topk_per_head,
     shplb_sparse_attn_prefill,
     shplb_strerror,

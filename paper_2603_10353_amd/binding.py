@@ -13,7 +13,7 @@ _LIB = None
 EXPORTS = [
     "shplb_num_rows", "shplb_workspace_bytes", "shplb_score_layout", "shplb_sel_row_ptr",
     "shplb_sched_num_workgroups", "shplb_block_scores", "shplb_select_topk_per_head",
-    "shplb_sparse_attn_prefill", "shplb_balance_heads", "shplb_strerror",
+    "shplb_sparse_attn_prefill", "shplb_balance_heads", "shplb_shift_budgets", "shplb_strerror",
 ]
 
 
@@ -81,6 +81,8 @@ def load_library():
     lib.shplb_select_topk_per_head.argtypes = [pp, vp, C.POINTER(i32), vp, vp, vp]
     lib.shplb_sparse_attn_prefill.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.shplb_balance_heads.argtypes = [C.POINTER(i64), i32, i32, i32, C.POINTER(i32), C.POINTER(i64)]
+    lib.shplb_shift_budgets.argtypes = [C.POINTER(C.c_double), i32, i32, i64, i32, i32, C.POINTER(i32),
+                                        C.POINTER(i64)]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = i32
     lib.shplb_strerror.argtypes = [i32]
@@ -210,3 +212,17 @@ def shplb_balance_heads(costs, n_parts: int, max_per_part: int = 0):
                                               loads.ctypes.data_as(C.POINTER(C.c_int64)) if n_parts > 0 else None),
            "shplb_balance_heads")
     return part, loads
+
+
+def shplb_shift_budgets(recovery, total: int, lower: int, step: int = 1):
+    """recovery: [n_heads, n_levels] float64.  Returns (budgets int32 [n_heads], number of moves)."""
+    r = np.ascontiguousarray(np.asarray(recovery, dtype=np.float64))
+    if r.ndim != 2:
+        raise ValueError("recovery must be [n_heads, n_levels]")
+    budgets = np.zeros(r.shape[0], np.int32)
+    moves = C.c_int64(0)
+    _check(load_library().shplb_shift_budgets(r.ctypes.data_as(C.POINTER(C.c_double)), r.shape[0], r.shape[1],
+                                              int(total), int(lower), int(step),
+                                              budgets.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(moves)),
+           "shplb_shift_budgets")
+    return budgets, int(moves.value)

@@ -231,6 +231,47 @@ int32_t shplb_balance_heads(const int64_t* costs, int32_t n, int32_t n_parts,
   return SHPLB_OK;
 }
 
+int32_t shplb_shift_budgets(const double* recovery, int32_t n_heads, int32_t n_levels,
+                            int64_t total, int32_t lower, int32_t step,
+                            int32_t* budgets_out, int64_t* n_moves_out) {
+  if (n_heads < 1 || n_levels < 1 || step < 1 || lower < 0) return SHPLB_E_SHAPE;
+  if (!recovery || !budgets_out) return SHPLB_E_NULL;
+  auto rec = [&](int32_t h, int64_t b) { return recovery[int64_t(h) * n_levels + b]; };
+  for (int32_t h = 0; h < n_heads; ++h)
+    for (int32_t b = 0; b < n_levels; ++b) {
+      if (!std::isfinite(rec(h, b))) return SHPLB_E_SHAPE;
+      if (b > 0 && rec(h, b) < rec(h, b - 1)) return SHPLB_E_SHAPE;
+    }
+  if (total < 0) return SHPLB_E_BUDGET;
+  std::vector<int64_t> b(n_heads);
+  for (int32_t h = 0; h < n_heads; ++h) b[h] = total / n_heads + (h < total % n_heads ? 1 : 0);
+  if (b[n_heads - 1] < lower || b[0] > n_levels - 1) return SHPLB_E_BUDGET;
+  int64_t moves = 0;
+  std::vector<double> now(n_heads);
+  for (;;) {
+    for (int32_t h = 0; h < n_heads; ++h) now[h] = rec(h, b[h]);
+    int32_t recv = 0;
+    for (int32_t h = 1; h < n_heads; ++h)
+      if (now[h] < now[recv]) recv = h;
+    int32_t give = -1;
+    for (int32_t h = 0; h < n_heads; ++h)
+      if (h != recv && b[h] - step >= lower && (give < 0 || now[h] > now[give])) give = h;
+    if (give < 0 || b[recv] + step > n_levels - 1) break;            // nothing left to move
+    const double give_after = rec(give, b[give] - step), recv_after = rec(recv, b[recv] + step);
+    double min_after = std::min(give_after, recv_after);
+    for (int32_t h = 0; h < n_heads; ++h)
+      if (h != give && h != recv) min_after = std::min(min_after, now[h]);
+    if (min_after < now[recv]) break;                                 // the move would not help
+    b[give] -= step;
+    b[recv] += step;
+    moves += 1;
+    if (give_after <= min_after) break;                               // the giver is the new minimum
+  }
+  for (int32_t h = 0; h < n_heads; ++h) budgets_out[h] = int32_t(b[h]);
+  if (n_moves_out) *n_moves_out = moves;
+  return SHPLB_OK;
+}
+
 const char* shplb_strerror(int32_t status) {
   switch (status) {
     case SHPLB_OK: return "ok";

@@ -127,3 +127,18 @@ def test_rising_and_falling_scores():
     k[:, 0, :] += (push[:, None] * u[None, :]).astype(np.float32)
     wl.k = bf16_bits_from_f32(k)
     full_parity(wl)
+
+
+def test_budgets_from_max_min_shifting():
+    # The producer feeds the consumer: budgets come out of shplb_shift_budgets run on synthetic
+    # recovery curves (saturating, head-dependent rate), 8 blocks per head on average, lower bound 2.
+    import paper_2603_10353_amd as S
+    nb, hq = 40, 8
+    rate = np.exp(np.random.default_rng(17).uniform(np.log(0.03), np.log(1.5), size=hq))
+    rec = 1.0 - np.exp(-np.outer(rate, np.arange(nb + 1)))
+    budgets, moves = S.shplb_shift_budgets(rec, total=8 * hq, lower=2)
+    bo, mo = orc.shift_budgets(rec, 8 * hq, 2)
+    np.testing.assert_array_equal(budgets, bo)
+    assert moves == mo and moves > 0 and budgets.min() >= 2 and budgets.sum() == 8 * hq
+    wl = make_custom([128 * nb - 9], hq, 2, 128, budgets.tolist(), seed=93, name="shifted_budgets")
+    full_parity(wl)

@@ -121,3 +121,47 @@ def test_config3_share_selection():
     heads, loads = bench.pick_config3_heads(S)
     assert len(heads) == 8 and heads[0] % 4 == 0 and heads[4] % 4 == 0
     assert orc.imbalance(loads) < 1.35
+
+
+def _monotone_curves(rng, n_heads, n_levels):
+    inc = rng.random((n_heads, n_levels)) ** rng.integers(1, 4, size=(n_heads, 1))
+    inc *= rng.random((n_heads, n_levels)) < 0.7                      # plateaus: exact ties between heads and steps
+    rec = np.cumsum(inc, axis=1)
+    return np.round(rec / np.maximum(rec[:, -1:], 1e-9) * rng.uniform(0.5, 1.0, size=(n_heads, 1)), 3)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_shift_budgets_bit_exact_vs_oracle(seed):
+    rng = np.random.default_rng(300 + seed)
+    for _ in range(60):
+        n_heads = int(rng.integers(1, 40))
+        n_levels = int(rng.integers(4, 300))
+        rec = _monotone_curves(rng, n_heads, n_levels)
+        lower = int(rng.integers(0, 4))
+        step = int(rng.integers(1, 4))
+        total = int(rng.integers(lower, n_levels - 1)) * n_heads + int(rng.integers(0, n_heads))
+        try:
+            bo, mo = orc.shift_budgets(rec, total, lower, step)
+        except ValueError:
+            with pytest.raises(S.ShplbError):
+                S.shplb_shift_budgets(rec, total, lower, step)
+            continue
+        bg, mg = S.shplb_shift_budgets(rec, total, lower, step)
+        np.testing.assert_array_equal(bg, bo)
+        assert mg == mo
+
+
+def test_shift_budgets_golden_and_errors(repo_root):
+    rec = [[0.00, 0.50, 0.80, 0.90, 0.95, 0.97, 0.98, 0.99, 1.00],
+           [0.00, 0.10, 0.20, 0.30, 0.40, 0.50, 0.60, 0.70, 0.80],
+           [0.00, 0.30, 0.55, 0.70, 0.80, 0.86, 0.90, 0.93, 0.95]]
+    b, n = S.shplb_shift_budgets(rec, 12, 1)
+    assert b.tolist() == [2, 6, 4] and n == 2
+    for bad, status in [(dict(recovery=[[0.0, 0.5, 0.4]], total=1, lower=0), -2),       # decreasing curve
+                        (dict(recovery=[[0.0, float("nan")]], total=1, lower=0), -2),
+                        (dict(recovery=rec, total=12, lower=1, step=0), -2),
+                        (dict(recovery=rec, total=30, lower=1), -3),                    # 10 per head: past the curves
+                        (dict(recovery=rec, total=3, lower=2), -3)]:                    # below the lower bound
+        with pytest.raises(S.ShplbError) as e:
+            S.shplb_shift_budgets(**bad)
+        assert e.value.status == status
