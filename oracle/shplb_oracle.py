@@ -36,12 +36,22 @@ What the paper fixes and what it leaves open
     iteration; a move that is made and leaves the giver as the (possibly tied)
     minimum ends it too; an indivisible total gives its remainder to the first heads.
 
+  * The recovery ratio of Section 2.4 (cumulative attention weight of the top-k keys) is
+    taken at block granularity: the mass of key block j for query block i is the
+    attention weight that the queries of block i put on the keys of block j, averaged
+    over the block's queries; a head's recovery at budget b is the mass of the b
+    heaviest blocks of a row, averaged over all queries of the head (rows with fewer
+    than b visible blocks recover everything).  The paper profiles tokens (k = 4096);
+    blocks are what the path's budgets count.
+
 Pins (tests/test_oracle_*.py): dense special case vs a textbook attention routine,
 row sums, constant-V, sink+diagonal special case, selection-order invariance,
 closed-form pooled scores, brute-force top-k, constructed ties, hand-worked greedy
 instance, exhaustive optimum on tiny partitions, cost closed form; budget shifting:
 hand-worked instance, identical curves, exhaustive max-min optimum for two heads,
-invariants and the no-further-move property on random monotone curves.
+invariants on random monotone curves; block mass: rows sum to one, closed form for
+constant keys, block sums of a textbook softmax; recovery curves: closed forms for
+uniform and one-hot rows, monotone and concave in the budget.
 Parity unpinned: how well pooled-score selection tracks true attention mass (needs
 the paper's models and data); only self-consistency is checked.
 """
@@ -306,3 +316,82 @@ def shift_budgets(recovery: np.ndarray, total: int, lower: int, step: int = 1) -
         if after[give] <= min(after):
             break                                                       # (i): the giver is the new minimum
     return np.asarray(b, dtype=np.int64), moves
+
+
+# --------------------------------------------------------------------------- recovery profile (Section 2.4)
+def block_mass(q_bits: np.ndarray, k_bits: np.ndarray, cu_seqlens: Sequence[int], block: int,
+               softmax_scale: Optional[float] = None, rows: Optional[Sequence[int]] = None
+               ) -> List[np.ndarray]:
+    """Attention weight per (query block, key block), Eq. 1 weights under the causal mask:
+    mass[s][h, i, j] = mean over the valid queries t of block i of sum over the keys u of
+    block j (u <= t) of softmax_t(q_t . k_u * scale).  One [Hq, nb, nb] fp64 array per
+    sequence, NaN where j > i and on rows not asked for (`rows`: global row indices as in
+    row_index(); None = all)."""
+    q = decode_bf16(q_bits)
+    k = decode_bf16(k_bits)
+    n_q_heads, n_kv_heads, d = q.shape[1], k.shape[1], q.shape[2]
+    group = n_q_heads // n_kv_heads
+    scale = 1.0 / math.sqrt(d) if softmax_scale is None else float(softmax_scale)
+    cu = [int(x) for x in cu_seqlens]
+    nbs = blocks_per_sequence(cu, block)
+    want = None if rows is None else set(int(r) for r in rows)
+    out = []
+    for s, nb in enumerate(nbs):
+        m = np.full((n_q_heads, nb, nb), np.nan)
+        for h in range(n_q_heads):
+            kh = k[cu[s]:cu[s + 1], h // group, :]
+            for i in range(nb):
+                if want is not None and row_index(cu, block, n_q_heads, s, h, i) not in want:
+                    continue
+                t0, t1 = cu[s] + i * block, min(cu[s] + (i + 1) * block, cu[s + 1])
+                logits = q[t0:t1, h, :] @ kh[:t1 - cu[s]].T * scale              # [queries, keys so far]
+                pos_q = np.arange(t0, t1)[:, None] - cu[s]
+                pos_k = np.arange(t1 - cu[s])[None, :]
+                logits = np.where(pos_k <= pos_q, logits, -np.inf)
+                w = np.exp(logits - logits.max(axis=1, keepdims=True))
+                w /= w.sum(axis=1, keepdims=True)
+                for j in range(i + 1):
+                    m[h, i, j] = w[:, j * block:(j + 1) * block].sum() / (t1 - t0)
+        out.append(m)
+    return out
+
+
+def recovery_curves(mass: List[np.ndarray], cu_seqlens: Sequence[int], block: int) -> np.ndarray:
+    """Recovery ratio per head and budget (Section 2.4, at block granularity):
+    curves[h][b] = mean over all queries of head h (all sequences) of the mass of the b
+    heaviest key blocks of the query's row; b = 0 .. max blocks.  A row with fewer than b
+    visible blocks recovers its whole mass."""
+    cu = [int(x) for x in cu_seqlens]
+    nbs = blocks_per_sequence(cu, block)
+    n_heads, n_levels = mass[0].shape[0], max(nbs) + 1
+    curves = np.zeros((n_heads, n_levels))
+    n_queries = 0
+    for s, nb in enumerate(nbs):
+        for i in range(nb):
+            n_valid = min(block, cu[s + 1] - cu[s] - i * block)
+            n_queries += n_valid
+            for h in range(n_heads):
+                heaviest_first = np.sort(mass[s][h, i, :i + 1])[::-1]
+                cum = np.concatenate([[0.0], np.cumsum(heaviest_first)])
+                row = np.full(n_levels, cum[-1])
+                row[:i + 2] = cum
+                curves[h] += n_valid * row
+    return curves / n_queries
+
+
+def selection_recovery(mass: List[np.ndarray], cu_seqlens: Sequence[int], block: int,
+                       sel_ptr: np.ndarray, sel_idx: np.ndarray) -> np.ndarray:
+    """Mean over all queries of a head of the mass its selected blocks hold: [n_heads]."""
+    cu = [int(x) for x in cu_seqlens]
+    nbs = blocks_per_sequence(cu, block)
+    n_heads = mass[0].shape[0]
+    got = np.zeros(n_heads)
+    n_queries = 0
+    for s, nb in enumerate(nbs):
+        for i in range(nb):
+            n_valid = min(block, cu[s + 1] - cu[s] - i * block)
+            n_queries += n_valid
+            for h in range(n_heads):
+                r = row_index(cu, block, n_heads, s, h, i)
+                got[h] += n_valid * mass[s][h, i, sel_idx[sel_ptr[r]:sel_ptr[r + 1]]].sum()
+    return got / n_queries
