@@ -10,6 +10,8 @@
  *                               work items dealt to compute units by descending cost
  *   shplb_balance_heads         greedy head-to-partition assignment (host)
  *   shplb_shift_budgets         max-min budget shifting: the producer of the budgets (host)
+ *   shplb_block_mass            offline recovery profile: attention weight per block pair
+ *   shplb_recovery_curves       recovery ratio per head and budget from that profile (host)
  *
  * Conventions
  *   - Every function returns an int32 status: 0 = OK, negative = error (see
@@ -144,6 +146,30 @@ SHPLB_API int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* 
                                   const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
                                   void* out, float* lse_out, void* sched_stats_out,
                                   void* workspace, void* stream);
+
+/* ---- offline profile ------------------------------------------------------- */
+
+/* Recovery profile (Section 2.4, at the granularity the budgets count): under full
+ * causal attention (Eq. 1), mass[s][h][i][j] = the attention weight that the valid
+ * queries of block i put on the keys of block j, averaged over those queries, for
+ * j <= i; every row sums to 1.  Entries with j > i are not written.  A dense pass
+ * (every key block of every row), fp32 softmax statistics, bf16 MFMA products.
+ *   q, k: device bf16.  mass_out: device fp32, laid out like the scores
+ *   (shplb_score_layout()). */
+SHPLB_API int32_t shplb_block_mass(const shplb_problem* p, const void* q, const void* k,
+                         float* mass_out, void* stream);
+
+/* Recovery ratio per head and budget from a block-mass profile:
+ * curves_out[h][b] = mean over all queries of head h (all sequences) of the mass of
+ * the b heaviest key blocks of the query's row, b = 0 .. n_levels-1; a row with
+ * fewer than b visible blocks recovers all of its mass.  Non-decreasing in b: the
+ * input shplb_shift_budgets takes.  All pointers are host memory.
+ *   mass: host fp32 in the layout shplb_block_mass writes (copied from the device
+ *   by the caller).  curves_out: [n_q_heads][n_levels] doubles, n_levels must be
+ *   max blocks per sequence + 1.
+ * Errors: SHPLB_E_NULL, SHPLB_E_SHAPE (also a wrong n_levels). */
+SHPLB_API int32_t shplb_recovery_curves(const shplb_problem* p, const float* mass, int32_t n_levels,
+                              double* curves_out);
 
 /* ---- host step ------------------------------------------------------------ */
 

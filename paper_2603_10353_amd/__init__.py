@@ -12,8 +12,10 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     shplb_balance_heads,
+    shplb_block_mass,
     shplb_block_scores,
     shplb_num_rows,
+    shplb_recovery_curves,
     shplb_sched_num_workgroups,
     shplb_score_layout,
     shplb_sel_row_ptr,

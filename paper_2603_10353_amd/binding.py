@@ -13,7 +13,8 @@ _LIB = None
 EXPORTS = [
     "shplb_num_rows", "shplb_workspace_bytes", "shplb_score_layout", "shplb_sel_row_ptr",
     "shplb_sched_num_workgroups", "shplb_block_scores", "shplb_select_topk_per_head",
-    "shplb_sparse_attn_prefill", "shplb_balance_heads", "shplb_shift_budgets", "shplb_strerror",
+    "shplb_sparse_attn_prefill", "shplb_balance_heads", "shplb_shift_budgets", "shplb_block_mass",
+    "shplb_recovery_curves", "shplb_strerror",
 ]
 
 
@@ -81,6 +82,8 @@ def load_library():
     lib.shplb_select_topk_per_head.argtypes = [pp, vp, C.POINTER(i32), vp, vp, vp]
     lib.shplb_sparse_attn_prefill.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.shplb_balance_heads.argtypes = [C.POINTER(i64), i32, i32, i32, C.POINTER(i32), C.POINTER(i64)]
+    lib.shplb_block_mass.argtypes = [pp, vp, vp, vp, vp]
+    lib.shplb_recovery_curves.argtypes = [pp, C.POINTER(C.c_float), i32, C.POINTER(C.c_double)]
     lib.shplb_shift_budgets.argtypes = [C.POINTER(C.c_double), i32, i32, i64, i32, i32, C.POINTER(i32),
                                         C.POINTER(i64)]
     for name in EXPORTS[:-1]:
@@ -226,3 +229,23 @@ def shplb_shift_budgets(recovery, total: int, lower: int, step: int = 1):
                                               budgets.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(moves)),
            "shplb_shift_budgets")
     return budgets, int(moves.value)
+
+
+def shplb_block_mass(p: Problem, q, k, mass_out, stream=None) -> None:
+    _check(load_library().shplb_block_mass(p.ref(), _dev(q), _dev(k), _dev(mass_out), _stream(stream)),
+           "shplb_block_mass")
+
+
+def shplb_recovery_curves(p: Problem, mass_host) -> np.ndarray:
+    """mass_host: float32 host array in the layout shplb_block_mass writes.  Returns float64 [n_q_heads, max_nb + 1]."""
+    m = np.ascontiguousarray(np.asarray(mass_host, dtype=np.float32)).reshape(-1)
+    off = shplb_score_layout(p)
+    if m.size != int(off[-1]):
+        raise ValueError("mass has %d floats, layout needs %d" % (m.size, int(off[-1])))
+    nbs = [-(-(int(p.cu[s + 1]) - int(p.cu[s])) // p.c.block) for s in range(len(p.cu) - 1)]
+    n_levels = max(nbs) + 1
+    curves = np.zeros((p.c.n_q_heads, n_levels), np.float64)
+    _check(load_library().shplb_recovery_curves(p.ref(), m.ctypes.data_as(C.POINTER(C.c_float)), n_levels,
+                                                curves.ctypes.data_as(C.POINTER(C.c_double))),
+           "shplb_recovery_curves")
+    return curves

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <functional>
 #include <numeric>
 #include <vector>
 
@@ -204,6 +205,44 @@ int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* q, const v
 
 // Greedy multiway partition of Section 3.3.  n is a head (or KV-group) count, so
 // the O(n * n_parts) scan for the least-loaded part is as good as a heap here.
+int32_t shplb_block_mass(const shplb_problem* p, const void* q, const void* k, float* mass_out, void* stream) {
+  if (!q || !k || !mass_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 15) return SHPLB_E_SHAPE;
+  return launch_block_mass(g, q, k, mass_out, static_cast<hipStream_t>(stream));
+}
+
+int32_t shplb_recovery_curves(const shplb_problem* p, const float* mass, int32_t n_levels, double* curves_out) {
+  if (!mass || !curves_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  if (n_levels != g.max_nb + 1) return SHPLB_E_SHAPE;
+  const SeqMeta& m = g.meta;
+  const int n_heads = m.n_q_heads;
+  std::fill(curves_out, curves_out + int64_t(n_heads) * n_levels, 0.0);
+  std::vector<double> row;
+  for (int s = 0; s < m.n_seq; ++s) {
+    const int nb = m.blk_begin[s + 1] - m.blk_begin[s];
+    const int len = m.tok_begin[s + 1] - m.tok_begin[s];
+    for (int h = 0; h < n_heads; ++h)
+      for (int i = 0; i < nb; ++i) {
+        const int n_valid = std::min(m.block, len - i * m.block);
+        const float* src = mass + m.score_off[s] + (int64_t(h) * nb + i) * nb;
+        row.assign(src, src + i + 1);
+        std::sort(row.begin(), row.end(), std::greater<double>());        // heaviest first
+        double* dst = curves_out + int64_t(h) * n_levels;
+        double cum = 0.0;
+        for (int b = 1; b < n_levels; ++b) {
+          if (b <= i + 1) cum += row[b - 1];
+          dst[b] += n_valid * cum;
+        }
+      }
+  }
+  for (int64_t x = 0; x < int64_t(n_heads) * n_levels; ++x) curves_out[x] /= double(g.total_tokens);
+  return SHPLB_OK;
+}
+
 int32_t shplb_balance_heads(const int64_t* costs, int32_t n, int32_t n_parts,
                             int32_t max_per_part, int32_t* part_of_out, int64_t* loads_out) {
   if (n < 0 || n_parts < 1 || max_per_part < 0) return SHPLB_E_SHAPE;

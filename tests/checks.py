@@ -7,6 +7,8 @@ SCORE_ATOL = 2e-5      # fp32 pooling + fp32 dot of 128 terms against the fp64 o
 SEL_WAIVER = 1e-5      # a swap is allowed only between scores this close to the row's threshold
 OUT_MAX_ABS = 2e-2     # bf16 inputs, bf16 P, fp32 accumulate
 OUT_MAX_REL = 1e-2     # max|diff| / max|oracle| per head
+MASS_RTOL = 2e-4      # block mass: fp32 exp2 of fp32 logits (|s| of a few tens) and fp32 sums of up to 16K terms
+MASS_ATOL = 1e-7
 LSE_ATOL = 4e-3        # l sums the bf16-rounded probabilities: relative error up to 2^-9, plus fp32 exp/log
 
 

@@ -56,6 +56,21 @@ class GpuRun:
                                     self.sel_idx if sel_idx is None else sel_idx,
                                     self.out, self.lse, self.stats, self.ws, torch.cuda.current_stream())
 
+    def mass_step(self):
+        """Offline recovery profile into its own buffer (same layout as the scores)."""
+        if not hasattr(self, "mass"):
+            self.mass = torch.full_like(self.scores, float("nan"))
+        S.shplb_block_mass(self.p, self.q, self.k, self.mass, torch.cuda.current_stream())
+
+    def mass_flat_host(self):
+        return self.mass.cpu().numpy()
+
+    def mass_host(self):
+        flat = self.mass_flat_host()
+        nbs = self.wl.n_blocks
+        return [flat[self.score_off[s]:self.score_off[s + 1]].reshape(self.wl.n_q_heads, nbs[s], nbs[s])
+                for s in range(self.wl.n_seq)]
+
     def run_all(self):
         self.scores_step()
         self.select_step()
