@@ -165,3 +165,17 @@ def test_shift_budgets_golden_and_errors(repo_root):
         with pytest.raises(S.ShplbError) as e:
             S.shplb_shift_budgets(**bad)
         assert e.value.status == status
+
+
+def test_recovery_curves_vs_oracle_on_host():
+    # Host entry point fed the oracle's own block masses (as fp32, in the library's layout).
+    from workloads import make_custom
+    wl = make_custom([64 * 5 + 9, 30, 64 * 2], 4, 2, 64, [2, 2, 2, 2], seed=44)
+    mass = orc.block_mass(wl.q, wl.k, wl.cu_seqlens, 64)
+    p = S.Problem(wl.cu_seqlens, 4, 2, 64)
+    flat = np.concatenate([np.nan_to_num(m, nan=0.0).astype(np.float32).reshape(-1) for m in mass])
+    got = S.shplb_recovery_curves(p, flat)
+    want = orc.recovery_curves([m.astype(np.float32).astype(np.float64) for m in mass], wl.cu_seqlens, 64)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-15)
+    with pytest.raises(ValueError):
+        S.shplb_recovery_curves(p, flat[:-1])
