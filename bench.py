@@ -113,6 +113,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the two short MFMA-only launches that measure what the matrix pipe sustains")
     ap.add_argument("--profile-pass", action="store_true",
                     help="also time the offline recovery profile (shplb_block_mass, a dense pass; not part of a step)")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -235,6 +237,27 @@ def main():
                      "kernel_ms": attn_ms},
         "host_input_generation_s": t_gen,
     }
+
+    if not args.no_mfma_ceiling:
+        # What the bf16 matrix pipe sustains on this chip with nothing else going on: the published
+        # peak is the roofline's denominator, this is the ceiling a kernel can actually approach.
+        n_probe, iters = 1024, 120000            # 0.13-0.17 s per launch: long enough for the clock to settle
+        scratch = torch.zeros(16 + n_probe * 2048, dtype=torch.uint8, device=dev)
+        ceiling = {}
+        for name, rnd in (("constant_operands", False), ("random_operands", True)):
+            S.shplb_probe_mfma_rate(rnd, iters // 4, n_probe, scratch, stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            S.shplb_probe_mfma_rate(rnd, iters, n_probe, scratch, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            clk = scratch[:16].cpu().numpy().view(np.uint64)
+            ceiling[name] = {"tflops": n_probe * 8 * 8 * iters * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12,
+                             "clock_mhz": float(clk[0]) / (float(clk[1]) * 0.01)}
+        ceiling["attention_frac_of_random_operand_rate"] = attn_tflops / ceiling["random_operands"]["tflops"]
+        result["mfma_ceiling"] = ceiling
+        del scratch
 
     if args.profile_pass:
         mass = torch.empty_like(scores)

@@ -206,6 +206,20 @@ SHPLB_API int32_t shplb_shift_budgets(const double* recovery, int32_t n_heads, i
                             int64_t total, int32_t lower, int32_t step,
                             int32_t* budgets_out, int64_t* n_moves_out);
 
+/* ---- diagnostic ------------------------------------------------------------ */
+
+/* Rate of the bf16 matrix pipe as this chip sustains it: launches n_workgroups
+ * workgroups of eight waves that issue 8 * iters v_mfma_f32_32x32x16_bf16 each on
+ * register operands and nothing else.  random_operands != 0: operands with random
+ * signs and mantissas and magnitudes around one (what attention multiplies);
+ * 0: one small constant.  The caller times the launch (FLOP = n_workgroups * 8 *
+ * 8 * iters * 32768) and may read the loop's span on workgroup 0 from scratch:
+ * uint64 [0] = shader clock cycles, [1] = the same span in 100 MHz ticks.
+ *   scratch: device, 16 + n_workgroups * 2048 bytes, 8-byte aligned.
+ * Errors: SHPLB_E_NULL, SHPLB_E_SHAPE (iters < 1, n_workgroups < 1). */
+SHPLB_API int32_t shplb_probe_mfma_rate(int32_t random_operands, int32_t iters, int32_t n_workgroups,
+                              void* scratch, void* stream);
+
 SHPLB_API const char* shplb_strerror(int32_t status);
 
 #ifdef __cplusplus

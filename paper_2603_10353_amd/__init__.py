@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     shplb_block_mass,
     shplb_block_scores,
     shplb_num_rows,
+    shplb_probe_mfma_rate,
     shplb_recovery_curves,
     shplb_sched_num_workgroups,
     shplb_score_layout,

@@ -14,7 +14,7 @@ EXPORTS = [
     "shplb_num_rows", "shplb_workspace_bytes", "shplb_score_layout", "shplb_sel_row_ptr",
     "shplb_sched_num_workgroups", "shplb_block_scores", "shplb_select_topk_per_head",
     "shplb_sparse_attn_prefill", "shplb_balance_heads", "shplb_shift_budgets", "shplb_block_mass",
-    "shplb_recovery_curves", "shplb_strerror",
+    "shplb_recovery_curves", "shplb_probe_mfma_rate", "shplb_strerror",
 ]
 
 
@@ -82,6 +82,7 @@ def load_library():
     lib.shplb_select_topk_per_head.argtypes = [pp, vp, C.POINTER(i32), vp, vp, vp]
     lib.shplb_sparse_attn_prefill.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.shplb_balance_heads.argtypes = [C.POINTER(i64), i32, i32, i32, C.POINTER(i32), C.POINTER(i64)]
+    lib.shplb_probe_mfma_rate.argtypes = [i32, i32, i32, vp, vp]
     lib.shplb_block_mass.argtypes = [pp, vp, vp, vp, vp]
     lib.shplb_recovery_curves.argtypes = [pp, C.POINTER(C.c_float), i32, C.POINTER(C.c_double)]
     lib.shplb_shift_budgets.argtypes = [C.POINTER(C.c_double), i32, i32, i64, i32, i32, C.POINTER(i32),
@@ -249,3 +250,8 @@ def shplb_recovery_curves(p: Problem, mass_host) -> np.ndarray:
                                                 curves.ctypes.data_as(C.POINTER(C.c_double))),
            "shplb_recovery_curves")
     return curves
+
+
+def shplb_probe_mfma_rate(random_operands: bool, iters: int, n_workgroups: int, scratch, stream=None) -> None:
+    _check(load_library().shplb_probe_mfma_rate(int(bool(random_operands)), int(iters), int(n_workgroups),
+                                                _dev(scratch), _stream(stream)), "shplb_probe_mfma_rate")

@@ -311,6 +311,13 @@ int32_t shplb_shift_budgets(const double* recovery, int32_t n_heads, int32_t n_l
   return SHPLB_OK;
 }
 
+int32_t shplb_probe_mfma_rate(int32_t random_operands, int32_t iters, int32_t n_workgroups, void* scratch,
+                              void* stream) {
+  if (!scratch) return SHPLB_E_NULL;
+  if (iters < 1 || n_workgroups < 1 || (reinterpret_cast<uintptr_t>(scratch) & 7)) return SHPLB_E_SHAPE;
+  return launch_mfma_rate(random_operands, iters, n_workgroups, scratch, static_cast<hipStream_t>(stream));
+}
+
 const char* shplb_strerror(int32_t status) {
   switch (status) {
     case SHPLB_OK: return "ok";

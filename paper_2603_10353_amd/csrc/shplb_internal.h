@@ -63,6 +63,7 @@ int32_t launch_select(const Geometry& g, const float* scores, const int64_t* sel
                       int32_t* sel_idx, hipStream_t stream);
 int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceLayout& w,
                      char* workspace, hipStream_t stream);
+int32_t launch_mfma_rate(int random_operands, int iters, int n_workgroups, void* scratch, hipStream_t stream);
 int32_t launch_block_mass(const Geometry& g, const void* q, const void* k, float* mass, hipStream_t stream);
 // The per-XCD work queues the ordering kernels build (device pointers into the workspace).
 struct WorkQueues {
