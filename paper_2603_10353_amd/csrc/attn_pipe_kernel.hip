@@ -78,10 +78,11 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 
   uint32_t my_items = 0, my_cost = 0;
   uint64_t t_first = 0, t_last = 0;
-  int queue = my_xcd(), exhausted = 0;   // work queue this workgroup currently draws from (thread 0 only)
+  const int home = my_xcd();
+  int empty_mask = 0;                    // queues this workgroup has found empty (thread 0 only)
 
   for (;;) {
-    if (tid == 0) s_item = next_item(wq, queue, exhausted);
+    if (tid == 0) s_item = next_item(wq, home, empty_mask);
     __syncthreads();
     const int row = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
     __syncthreads();

@@ -7,7 +7,8 @@
 // free.  MI355X has eight dies (XCDs), each with its own L2, so the sorted list is split
 // into one queue per die: all rows that stream one KV head of one sequence share a home
 // die, whose L2 then sees that K/V once.  A workgroup drains its die's queue first and
-// then helps the next die (see next_item()), which keeps the greedy's balance.
+// then helps whichever die has the most items left (see next_item()), which keeps the
+// greedy's balance when the dies' queues hold very different amounts of work.
 //
 // Two stable counting sorts, least significant key first:
 //   1. by descending cost (per-256-row histograms, one-workgroup scan, scatter);

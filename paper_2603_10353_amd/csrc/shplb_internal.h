@@ -104,18 +104,46 @@ __device__ __forceinline__ int xcd_of_row(const SeqMeta& m, int32_t row) {
   return stream * per + i % per;
 }
 
-// Next work item for a persistent workgroup (called by one thread): take from the current
-// queue (first the home XCD's), move on to the next die's queue when it is exhausted.
-// Returns the row, or -1 when every queue is empty.
-__device__ __forceinline__ int32_t next_item(const WorkQueues& wq, int& queue, int& exhausted) {
-  while (exhausted < kXcds) {
-    const int begin = wq.queue_begin[queue], end = wq.queue_begin[queue + 1];
-    const uint32_t t = atomicAdd(wq.tickets + queue * kTicketStride, 1u);
-    if (t < uint32_t(end - begin)) return wq.order[begin + int(t)];
-    queue = (queue + 1) % kXcds;
-    ++exhausted;
+// The queue with the most items left, other than those in empty_mask (ties: the first one
+// after home), or -1.  Counts are read with device-scope loads and may be a little old.
+// Kept out of line: it runs a few times per workgroup, at the end of a launch, and inlined
+// it costs the attention kernels registers across their whole item loop.
+__device__ __attribute__((noinline)) int fullest_queue(const int32_t* queue_begin, const uint32_t* tickets,
+                                                       int home, int empty_mask) {
+  int most = 0, pick = -1;
+  for (int d = 1; d < kXcds; ++d) {
+    const int x = (home + d) % kXcds;
+    if (empty_mask & 1 << x) continue;
+    const uint32_t size = uint32_t(queue_begin[x + 1] - queue_begin[x]);
+    const uint32_t taken = __hip_atomic_load(tickets + x * kTicketStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int left = taken < size ? int(size - taken) : 0;
+    if (left > most) {
+      most = left;
+      pick = x;
+    }
   }
-  return -1;
+  return pick;
+}
+
+// Next work item for a persistent workgroup (called by one thread).  A workgroup draws from
+// its home die's queue until that is empty; from then on every item comes from the queue
+// that has the most items left at that moment.  Helpers so spread over the dies that still
+// have work in proportion to what is left there, and no queue is left for last with its
+// heavy items still in it.  An old count only affects which queue is tried, the ticket
+// decides.  A queue whose ticket came back past its end is never tried again, so the loop
+// ends after at most kXcds misses.  Returns the row, or -1 when every queue is empty.
+__device__ __forceinline__ int32_t next_item(const WorkQueues& wq, int home, int& empty_mask) {
+  int pick = home;
+  for (;;) {
+    if (empty_mask & 1 << home) {
+      pick = fullest_queue(wq.queue_begin, wq.tickets, home, empty_mask);
+      if (pick < 0) return -1;
+    }
+    const int begin = wq.queue_begin[pick], end = wq.queue_begin[pick + 1];
+    const uint32_t t = atomicAdd(wq.tickets + pick * kTicketStride, 1u);
+    if (t < uint32_t(end - begin)) return wq.order[begin + int(t)];
+    empty_mask |= 1 << pick;
+  }
 }
 
 __device__ __forceinline__ int my_xcd() {
