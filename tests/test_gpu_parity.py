@@ -79,6 +79,17 @@ def test_dense_budget_equals_dense_attention():
     compare_output(run.out_host(), ref)
 
 
+def test_long_and_short_rows_mixed():
+    # Rows of up to 41 selected blocks beside rows of 2 or 3: dense, wide and narrow heads, a
+    # ragged tail, a second shorter sequence, GQA.  Work items of very different length go
+    # through the queues together; every selected block is visited exactly once.
+    wl = make_custom([128 * 40 + 37, 128 * 11], 4, 2, 128, [999, 999, 23, 3, 999, 18, 2, 7], seed=61, name="mixed")
+    run = full_parity(wl)
+    st = run.stats_host()
+    assert st["cost_blocks"].sum() == run.sel_ptr_host[-1]
+    assert st["n_items"].sum() == run.rows
+
+
 def test_explicit_softmax_scale():
     wl = make_custom([700], 2, 2, 64, [3, 6], seed=41, name="scale")
     full_parity(wl, softmax_scale=0.05)
