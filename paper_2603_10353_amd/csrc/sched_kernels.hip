@@ -157,6 +157,57 @@ __global__ __launch_bounds__(kOrderChunk) void queue_scatter_kernel(
   order[queue_begin[x] + xcd_hist[blockIdx.x * kXcds + x] + rank] = row;
 }
 
+// Both sorts in one workgroup, for launches of few rows (prompts of a few thousand tokens, a
+// part's share of a layer), where five dependent launches would cost more than the sorting.
+// One counting sort over the combined key (die, descending cost) with the histogram in LDS:
+// count, scan, place.  Rows of equal key are placed in the order their atomics arrive, so
+// unlike the two-sort path the order among equal costs is not fixed; it decides only which
+// workgroup takes which of two equally long rows.
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallKeys = 16384;     // LDS histogram entries: kXcds * (cost bins) must fit
+constexpr int kSmallRows = 16384;
+
+__global__ __launch_bounds__(kSmallThreads) void order_small_kernel(
+    SeqMeta meta, const int64_t* __restrict__ sel_ptr, int32_t* __restrict__ order,
+    int32_t* __restrict__ queue_begin, uint32_t* __restrict__ tickets, int rows, int n_bins) {
+  __shared__ int32_t slot[kSmallKeys];               // count per key, then next free position per key
+  __shared__ int32_t wave_sum[kSmallThreads / 64];
+  const int tid = threadIdx.x;
+  const int n_keys = kXcds * n_bins;
+  for (int x = tid; x < n_keys; x += kSmallThreads) slot[x] = 0;
+  if (tid < kXcds) tickets[tid * kTicketStride] = 0;
+  __syncthreads();
+  auto key_of = [&](int row) {
+    return xcd_of_row(meta, row) * n_bins + (n_bins - 1 - min(cost_bin(sel_ptr, row), n_bins - 1));
+  };
+  for (int row = tid; row < rows; row += kSmallThreads) atomicAdd(&slot[key_of(row)], 1);
+  __syncthreads();
+  // exclusive scan over the keys: a thread owns a run of consecutive keys
+  const int per = (n_keys + kSmallThreads - 1) / kSmallThreads;
+  const int k0 = min(tid * per, n_keys), k1 = min(k0 + per, n_keys);
+  int32_t mine = 0;
+  for (int x = k0; x < k1; ++x) mine += slot[x];
+  int32_t inc = mine;                                // inclusive scan of the threads' sums inside the wave
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int32_t up = __shfl_up(inc, d);
+    if ((tid & 63) >= d) inc += up;
+  }
+  if ((tid & 63) == 63) wave_sum[tid >> 6] = inc;
+  __syncthreads();
+  int32_t run = inc - mine;
+  for (int w = 0; w < (tid >> 6); ++w) run += wave_sum[w];
+  for (int x = k0; x < k1; ++x) {
+    const int32_t c = slot[x];
+    slot[x] = run;
+    if (x % n_bins == 0) queue_begin[x / n_bins] = run;   // first key of a die: its queue starts here
+    run += c;
+  }
+  if (tid == 0) queue_begin[kXcds] = rows;
+  __syncthreads();
+  for (int row = tid; row < rows; row += kSmallThreads) order[atomicAdd(&slot[key_of(row)], 1)] = row;
+}
+
 }  // namespace
 
 int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceLayout& w,
@@ -171,6 +222,12 @@ int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceL
   int32_t* xcd_hist = reinterpret_cast<int32_t*>(workspace + w.xcd_hist);
   int32_t* queue_begin = reinterpret_cast<int32_t*>(workspace + w.queue_begin);
   uint32_t* tickets = reinterpret_cast<uint32_t*>(workspace + w.tickets);
+  if (rows <= kSmallRows && kXcds * n_bins <= kSmallKeys) {
+    hipLaunchKernelGGL(order_small_kernel, dim3(1), dim3(kSmallThreads), 0, stream, g.meta, sel_ptr, order,
+                       queue_begin, tickets, rows, n_bins);
+    if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
+    return SHPLB_OK;
+  }
   hipLaunchKernelGGL(order_hist_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, sel_ptr, hist, xcd_hist,
                      rows, n_bins);
   hipLaunchKernelGGL(order_scan_kernel, dim3(1), dim3(1024), 0, stream, hist, bin_start, n_chunks, n_bins);
