@@ -117,6 +117,9 @@ def main():
                     help="skip the two short MFMA-only launches that measure what the matrix pipe sustains")
     ap.add_argument("--profile-pass", action="store_true",
                     help="also time the offline recovery profile (shplb_block_mass, a dense pass; not part of a step)")
+    ap.add_argument("--split-slots", type=int, default=0,
+                    help="run the attention step through shplb_sparse_attn_prefill_split with this many "
+                         "partial-result slots (long rows cut along the keys; block 128 only); 0 = whole rows")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -136,6 +139,8 @@ def main():
     cfg = WORKLOADS[args.workload]
     t_gen = time.perf_counter()
     extra = {}
+    if args.split_slots:
+        extra["split_slots"] = args.split_slots
     if cfg == 3:
         heads, loads = pick_config3_heads(S)
         wl = make_workload(3, q_heads=heads)
@@ -151,7 +156,8 @@ def main():
     q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
     p = S.Problem(wl.cu_seqlens, wl.n_q_heads, wl.n_kv_heads, wl.block, wl.head_dim)
     rows = S.shplb_num_rows(p)
-    ws = torch.empty(S.shplb_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    ws_bytes = S.shplb_split_workspace_bytes(p, args.split_slots) if args.split_slots else S.shplb_workspace_bytes(p)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     score_off = S.shplb_score_layout(p)
     scores = torch.empty(int(score_off[-1]), dtype=torch.float32, device=dev)
     sel_ptr_h = S.shplb_sel_row_ptr(p, wl.budgets)
@@ -173,7 +179,11 @@ def main():
         S.shplb_select_topk_per_head(p, scores, wl.budgets, sel_ptr, sel_idx, stream)
         if ev:
             ev[2].record()
-        S.shplb_sparse_attn_prefill(p, q, k, v, sel_ptr, sel_idx, out, lse, stats, ws, stream)
+        if args.split_slots:
+            S.shplb_sparse_attn_prefill_split(p, q, k, v, sel_ptr, sel_idx, out, lse, stats, ws, args.split_slots,
+                                              stream)
+        else:
+            S.shplb_sparse_attn_prefill(p, q, k, v, sel_ptr, sel_idx, out, lse, stats, ws, stream)
         if ev:
             ev[3].record()
 

@@ -147,6 +147,30 @@ SHPLB_API int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* 
                                   void* out, float* lse_out, void* sched_stats_out,
                                   void* workspace, void* stream);
 
+/* The same attention step with long rows cut along their selected key blocks
+ * (the partition of Section 3.3 applied below the row: a work item is a row or a
+ * piece of one).  Rows that select more than max(16, ceil(2 * total / split_slots))
+ * blocks, total = all selected blocks of the call, are cut into near-equal pieces;
+ * each piece is dealt to a workgroup like a row, leaves its unnormalised result,
+ * reference exponent and denominator in one of `split_slots` slots of the workspace
+ * (65 KB each), and a merge pass after the attention launch combines the pieces
+ * of a row in piece order (the softmax of Eq. 1 over the union of their keys).
+ * Results equal those of shplb_sparse_attn_prefill up to fp32 rounding of the
+ * merge and are bit-identical from run to run.  Finer items end a launch more
+ * evenly; the slots and the merge cost HBM traffic: measured, whole rows were
+ * faster on every shape tried, so this is an option, not the default.
+ *   split_slots: 2 .. 65536; block must be 128.
+ *   workspace: device, shplb_split_workspace_bytes(p, split_slots) bytes.
+ *   Other arguments as for shplb_sparse_attn_prefill; sched_stats_out counts
+ *   pieces as items.
+ * Errors: SHPLB_E_UNSUPPORTED for split_slots out of range or block != 128. */
+SHPLB_API int32_t shplb_split_workspace_bytes(const shplb_problem* p, int32_t split_slots,
+                                    int64_t* bytes_out /*host*/);
+SHPLB_API int32_t shplb_sparse_attn_prefill_split(const shplb_problem* p, const void* q, const void* k,
+                                        const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
+                                        void* out, float* lse_out, void* sched_stats_out,
+                                        void* workspace, int32_t split_slots, void* stream);
+
 /* ---- offline profile ------------------------------------------------------- */
 
 /* Recovery profile (Section 2.4, at the granularity the budgets count): under full

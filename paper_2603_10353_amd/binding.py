@@ -13,7 +13,8 @@ _LIB = None
 EXPORTS = [
     "shplb_num_rows", "shplb_workspace_bytes", "shplb_score_layout", "shplb_sel_row_ptr",
     "shplb_sched_num_workgroups", "shplb_block_scores", "shplb_select_topk_per_head",
-    "shplb_sparse_attn_prefill", "shplb_balance_heads", "shplb_shift_budgets", "shplb_block_mass",
+    "shplb_sparse_attn_prefill", "shplb_split_workspace_bytes", "shplb_sparse_attn_prefill_split",
+    "shplb_balance_heads", "shplb_shift_budgets", "shplb_block_mass",
     "shplb_recovery_curves", "shplb_probe_mfma_rate", "shplb_strerror",
 ]
 
@@ -81,6 +82,8 @@ def load_library():
     lib.shplb_block_scores.argtypes = [pp, vp, vp, vp, vp, vp]
     lib.shplb_select_topk_per_head.argtypes = [pp, vp, C.POINTER(i32), vp, vp, vp]
     lib.shplb_sparse_attn_prefill.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.shplb_split_workspace_bytes.argtypes = [pp, i32, C.POINTER(i64)]
+    lib.shplb_sparse_attn_prefill_split.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.shplb_balance_heads.argtypes = [C.POINTER(i64), i32, i32, i32, C.POINTER(i32), C.POINTER(i64)]
     lib.shplb_probe_mfma_rate.argtypes = [i32, i32, i32, vp, vp]
     lib.shplb_block_mass.argtypes = [pp, vp, vp, vp, vp]
@@ -204,6 +207,23 @@ def shplb_sparse_attn_prefill(p: Problem, q, k, v, sel_ptr, sel_idx, out, lse_ou
                                                     _dev(sel_idx), _dev(out), _dev(lse_out),
                                                     _dev(sched_stats_out), _dev(workspace), _stream(stream)),
            "shplb_sparse_attn_prefill")
+
+
+def shplb_split_workspace_bytes(p: Problem, split_slots: int) -> int:
+    out = C.c_int64(0)
+    _check(load_library().shplb_split_workspace_bytes(p.ref(), int(split_slots), C.byref(out)),
+           "shplb_split_workspace_bytes")
+    return int(out.value)
+
+
+def shplb_sparse_attn_prefill_split(p: Problem, q, k, v, sel_ptr, sel_idx, out, lse_out=None,
+                                    sched_stats_out=None, workspace=None, split_slots: int = 0,
+                                    stream=None) -> None:
+    _check(load_library().shplb_sparse_attn_prefill_split(p.ref(), _dev(q), _dev(k), _dev(v), _dev(sel_ptr),
+                                                          _dev(sel_idx), _dev(out), _dev(lse_out),
+                                                          _dev(sched_stats_out), _dev(workspace),
+                                                          int(split_slots), _stream(stream)),
+           "shplb_sparse_attn_prefill_split")
 
 
 def shplb_balance_heads(costs, n_parts: int, max_per_part: int = 0):

@@ -60,13 +60,21 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g) {
   return SHPLB_OK;
 }
 
-WorkspaceLayout make_layout(const Geometry& g) {
+WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots) {
   WorkspaceLayout w;
   int64_t off = 0;
   w.qbar = off; off += align256(int64_t(g.meta.n_q_heads) * g.total_blocks * kHeadDim * 6);
   w.kbar = off; off += align256(int64_t(g.meta.n_kv_heads) * g.total_blocks * kHeadDim * 6);
   w.order_by_cost = off; off += align256(g.rows * 4);
-  w.order = off; off += align256(g.rows * 4);
+  // Items: one per row plus the extra pieces of split rows.  split_length() keeps the pieces
+  // within whatever number of slots it is given.
+  w.slot_capacity = g.meta.block == kSplitBlock ? std::max<int32_t>(split_slots, 0) : 0;
+  w.item_capacity = g.rows + w.slot_capacity;
+  w.items = off; off += align256(w.item_capacity * int64_t(sizeof(ItemRec)));
+  w.split_rows = off; off += align256((w.slot_capacity / 2 + 1) * int64_t(sizeof(SplitRow)));
+  w.split_count = off; off += 256;
+  w.part_o = off; off += align256(w.slot_capacity * kSlotFloatsO * 4);
+  w.part_ml = off; off += align256(w.slot_capacity * kSlotFloatsML * 4);
   const int64_t n_chunks = (g.rows + kOrderChunk - 1) / kOrderChunk;
   w.hist = off; off += align256(n_chunks * kCostBins * 4);
   w.bin_start = off; off += align256(int64_t(kCostBins) * 4);
@@ -179,10 +187,11 @@ int32_t shplb_select_topk_per_head(const shplb_problem* p, const float* scores,
   return launch_select(g, scores, sel_ptr, sel_idx_out, static_cast<hipStream_t>(stream));
 }
 
-int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* q, const void* k,
-                                  const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
-                                  void* out, float* lse_out, void* sched_stats_out,
-                                  void* workspace, void* stream) {
+namespace {
+
+int32_t attention_entry(const shplb_problem* p, const void* q, const void* k, const void* v,
+                        const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse_out,
+                        void* sched_stats_out, void* workspace, int32_t split_slots, void* stream) {
   if (!q || !k || !v || !sel_ptr || !sel_idx || !out || !workspace) return SHPLB_E_NULL;
   Geometry g;
   if (int32_t st = make_geometry(p, &g)) return st;
@@ -192,15 +201,48 @@ int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* q, const v
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return SHPLB_E_SHAPE;
   const int32_t n_wg = persistent_workgroups();
   if (n_wg < 0) return n_wg;
-  const WorkspaceLayout w = make_layout(g);
+  const WorkspaceLayout w = make_layout(g, split_slots);
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (int32_t rc = launch_order(g, sel_ptr, w, ws, st)) return rc;
-  const WorkQueues wq{reinterpret_cast<const int32_t*>(ws + w.order),
+  const WorkQueues wq{reinterpret_cast<const ItemRec*>(ws + w.items),
                       reinterpret_cast<const int32_t*>(ws + w.queue_begin),
                       reinterpret_cast<uint32_t*>(ws + w.tickets)};
-  return launch_attention(g, q, k, v, sel_ptr, sel_idx, out, lse_out,
-                          static_cast<shplb_wg_stats*>(sched_stats_out), wq, n_wg, st);
+  const SplitBuffers sb{reinterpret_cast<float*>(ws + w.part_o), reinterpret_cast<float*>(ws + w.part_ml),
+                        reinterpret_cast<const SplitRow*>(ws + w.split_rows),
+                        reinterpret_cast<const SplitCounters*>(ws + w.split_count), int32_t(w.slot_capacity)};
+  if (int32_t rc = launch_attention(g, q, k, v, sel_ptr, sel_idx, out, lse_out,
+                                    static_cast<shplb_wg_stats*>(sched_stats_out), wq, sb, n_wg, st))
+    return rc;
+  return w.slot_capacity > 0 ? launch_merge(g, sb, out, lse_out, st) : SHPLB_OK;
+}
+
+}  // namespace
+
+int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* q, const void* k,
+                                  const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
+                                  void* out, float* lse_out, void* sched_stats_out,
+                                  void* workspace, void* stream) {
+  return attention_entry(p, q, k, v, sel_ptr, sel_idx, out, lse_out, sched_stats_out, workspace, 0, stream);
+}
+
+int32_t shplb_split_workspace_bytes(const shplb_problem* p, int32_t split_slots, int64_t* bytes_out) {
+  if (!bytes_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  if (split_slots < 2 || split_slots > kSplitSlotsMax || g.meta.block != kSplitBlock) return SHPLB_E_UNSUPPORTED;
+  *bytes_out = make_layout(g, split_slots).total;
+  return SHPLB_OK;
+}
+
+int32_t shplb_sparse_attn_prefill_split(const shplb_problem* p, const void* q, const void* k,
+                                        const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
+                                        void* out, float* lse_out, void* sched_stats_out,
+                                        void* workspace, int32_t split_slots, void* stream) {
+  if (!p) return SHPLB_E_NULL;
+  if (split_slots < 2 || split_slots > kSplitSlotsMax || p->block != kSplitBlock) return SHPLB_E_UNSUPPORTED;
+  return attention_entry(p, q, k, v, sel_ptr, sel_idx, out, lse_out, sched_stats_out, workspace, split_slots,
+                         stream);
 }
 
 // Greedy multiway partition of Section 3.3.  n is a head (or KV-group) count, so

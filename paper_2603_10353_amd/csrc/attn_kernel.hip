@@ -79,9 +79,10 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   for (;;) {
     if (tid == 0) s_item = next_item(wq, home, empty_mask);
     __syncthreads();
-    const int row = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
+    const int pos = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
     __syncthreads();
-    if (row < 0) break;
+    if (pos < 0) break;
+    const int row = __builtin_amdgcn_readfirstlane(wq.items[pos].row);   // rows are never split at this block size
     int s, h, i, nb;
     decode_row(meta, row, s, h, i, nb);
     const int g = h / group;
@@ -297,9 +298,9 @@ void launch_one(const Geometry& g, const void* q, const void* k, const void* v, 
 
 int32_t launch_attention(const Geometry& g, const void* q, const void* k, const void* v,
                          const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                         shplb_wg_stats* stats, WorkQueues wq, int32_t n_wg, hipStream_t stream) {
+                         shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg, hipStream_t stream) {
   if (g.meta.block == 128)
-    launch_attention_pipe128(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, wq, n_wg, stream);
+    launch_attention_pipe128(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, wq, sb, n_wg, stream);
   else
     launch_one<64>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, wq, n_wg, stream);
   if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;

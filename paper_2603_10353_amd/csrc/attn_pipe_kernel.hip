@@ -39,7 +39,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                       const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                       const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
                       uint16_t* __restrict__ out, float* __restrict__ lse,
-                      shplb_wg_stats* __restrict__ stats, WorkQueues wq, int64_t total_tokens,
+                      shplb_wg_stats* __restrict__ stats, WorkQueues wq, SplitBuffers sb, int64_t total_tokens,
                       float scale_log2) {
   constexpr int BQ = 128;
   constexpr int kWaves = 4 / NT;
@@ -98,15 +98,21 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   for (;;) {
     if (tid == 0) s_item = next_item(wq, home, empty_mask);
     __syncthreads();
-    const int row = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
+    const int pos = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
     __syncthreads();
-    if (row < 0) break;
+    if (pos < 0) break;
+    // the item: a row, or a piece of one (then it covers part of the row's selection and
+    // leaves a partial result in a slot instead of the output)
+    const ItemRec* item = wq.items + pos;
+    const int row = __builtin_amdgcn_readfirstlane(item->row);
+    const int n_sel = __builtin_amdgcn_readfirstlane(item->n_sel);
+    const int64_t sel_begin = item->sel_begin;
+    const int slot = __builtin_amdgcn_readfirstlane(item->slot);
+    if (row < 0 || row >= meta.blk_begin[meta.n_seq] * meta.n_q_heads || slot >= sb.slot_capacity) continue;
     int s, h, i, nb;
     decode_row(meta, row, s, h, i, nb);
     const int g = h / group;
     const int seq_begin = meta.tok_begin[s], seq_end = meta.tok_begin[s + 1];
-    const int64_t sel_begin = sel_ptr[row];
-    const int n_sel = int(sel_ptr[row + 1] - sel_begin);
     const int n_tiles = n_sel * 2;                     // two 64-key tiles per 128-token block: always even
     if (n_sel <= 0) continue;
     if (my_items == 0) t_first = wall_clock64();
@@ -379,7 +385,24 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const float l_tot = pair_sum(l_run[nt]);
-      if (q_tok[nt] < seq_end) {
+      if (slot >= 0) {
+        // a piece of a split row: O and l as they stand (relative to 2^m_ref), for merge_kernel
+        const int q_in = wave * QW + 32 * nt + n;
+        float* dst = sb.part_o + int64_t(slot) * kSlotFloatsO + q_in * kHeadDim + 4 * hi;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const f32x4 w = {acc_o[dt][nt][4 * rq], acc_o[dt][nt][4 * rq + 1], acc_o[dt][nt][4 * rq + 2],
+                             acc_o[dt][nt][4 * rq + 3]};
+            *reinterpret_cast<f32x4*>(dst + 32 * dt + 8 * rq) = w;
+          }
+        if (hi == 0) {
+          float* ml = sb.part_ml + int64_t(slot) * kSlotFloatsML;
+          ml[q_in] = m_ref[nt];
+          ml[128 + q_in] = l_tot;
+        }
+      } else if (q_tok[nt] < seq_end) {
         const float inv = 1.0f / l_tot;
         uint16_t* dst = out + int64_t(q_tok[nt]) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
 #pragma unroll
@@ -419,12 +442,13 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 
 void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
                               const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                              shplb_wg_stats* stats, WorkQueues wq, int32_t n_wg, hipStream_t stream) {
+                              shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg,
+                              hipStream_t stream) {
   const float scale_log2 = g.scale * 1.4426950408889634f;
   hipLaunchKernelGGL((attn_pipe_kernel<SHPLB_PIPE_NT>), dim3(n_wg), dim3(256 / SHPLB_PIPE_NT), 0, stream,
                      g.meta, g.st, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                      static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
-                     stats, wq, g.total_tokens, scale_log2);
+                     stats, wq, sb, g.total_tokens, scale_log2);
 }
 
 }  // namespace shplb

@@ -14,7 +14,15 @@
 //   1. by descending cost (per-256-row histograms, one-workgroup scan, scatter);
 //   2. by home die (8 bins; its histogram is accumulated by the first scatter).
 // Equal keys keep their row order (head-major, then query block), so items that stream
-// the same K/V blocks sit next to each other in a queue.  Everything is deterministic.
+// the same K/V blocks sit next to each other in a queue.
+//
+// When the caller provides slots for partial results (shplb_sparse_attn_prefill_split), rows
+// longer than split_length() are cut along their selected key blocks into near-equal pieces,
+// each an item of its own (sort 2 counts and places pieces instead of rows; the pieces of a
+// row sit next to each other, where the row would).  A piece leaves a partial result in a
+// slot of the workspace and merge_kernel combines the pieces of a row.  Slots and the list of
+// split rows are handed out through atomic counters, so their numbering varies between runs;
+// what is computed does not depend on it.
 #include "shplb_internal.h"
 
 namespace shplb {
@@ -87,12 +95,12 @@ __global__ __launch_bounds__(1024) void order_scan_kernel(
 }
 
 // Sort 1, pass 3: scatter.  Position = rows in costlier bins + rows of the same bin in
-// earlier chunks + rows of the same bin earlier in this chunk.  Counts the row into the
-// die histogram of the chunk its position falls in (sort 2, pass 1).
+// earlier chunks + rows of the same bin earlier in this chunk.  Counts the row's pieces into
+// the die histogram of the chunk its position falls in (sort 2, pass 1).
 __global__ __launch_bounds__(kOrderChunk) void order_scatter_kernel(
     SeqMeta meta, const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ hist,
     const int32_t* __restrict__ bin_start, int32_t* __restrict__ order_by_cost,
-    int32_t* __restrict__ xcd_hist, int rows, int n_bins) {
+    int32_t* __restrict__ xcd_hist, int rows, int n_bins, int slot_capacity) {
   __shared__ int32_t bins[kOrderChunk];
   const int row = blockIdx.x * kOrderChunk + threadIdx.x;
   const int bin = row < rows ? min(cost_bin(sel_ptr, row), n_bins - 1) : -1;
@@ -103,14 +111,16 @@ __global__ __launch_bounds__(kOrderChunk) void order_scatter_kernel(
   for (int x = 0; x < int(threadIdx.x); ++x) rank += bins[x] == bin;
   const int pos = bin_start[bin] + hist[int64_t(blockIdx.x) * n_bins + bin] + rank;
   order_by_cost[pos] = row;
-  atomicAdd(&xcd_hist[(pos / kOrderChunk) * kXcds + xcd_of_row(meta, row)], 1);
+  const int64_t split_len = split_length(sel_ptr[rows] - sel_ptr[0], slot_capacity);
+  const int pieces = pieces_of(sel_ptr[row + 1] - sel_ptr[row], split_len);
+  atomicAdd(&xcd_hist[(pos / kOrderChunk) * kXcds + xcd_of_row(meta, row)], pieces);
 }
 
 // Sort 2, pass 2 (one workgroup of 8 waves, wave x scans die x): exclusive prefix of the
-// die histogram over chunks, queue boundaries, and fresh tickets.
+// die histogram over chunks, queue boundaries, fresh tickets and split counters.
 __global__ __launch_bounds__(64 * kXcds) void queue_scan_kernel(
     int32_t* __restrict__ xcd_hist, int32_t* __restrict__ queue_begin, uint32_t* __restrict__ tickets,
-    int n_chunks) {
+    SplitCounters* __restrict__ split_count, int n_chunks) {
   __shared__ int32_t total[kXcds];
   const int x = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int32_t carry = 0;
@@ -132,6 +142,8 @@ __global__ __launch_bounds__(64 * kXcds) void queue_scan_kernel(
   }
   __syncthreads();
   if (threadIdx.x == 0) {
+    split_count->n_slots = 0;
+    split_count->n_rows = 0;
     int32_t run = 0;
     for (int d = 0; d < kXcds; ++d) {
       queue_begin[d] = run;
@@ -141,20 +153,49 @@ __global__ __launch_bounds__(64 * kXcds) void queue_scan_kernel(
   }
 }
 
-// Sort 2, pass 3: scatter the cost-sorted rows into their die's queue.
+// Sort 2, pass 3: write the items of the cost-sorted rows into their die's queue.  A row's
+// place is the number of pieces of earlier rows of the same die; a split row takes a run of
+// slots and an entry in the list the merge works through.
 __global__ __launch_bounds__(kOrderChunk) void queue_scatter_kernel(
-    SeqMeta meta, const int32_t* __restrict__ order_by_cost, const int32_t* __restrict__ xcd_hist,
-    const int32_t* __restrict__ queue_begin, int32_t* __restrict__ order, int rows) {
+    SeqMeta meta, const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ order_by_cost,
+    const int32_t* __restrict__ xcd_hist, const int32_t* __restrict__ queue_begin, ItemRec* __restrict__ items,
+    SplitRow* __restrict__ split_rows, SplitCounters* __restrict__ split_count, int rows, int item_capacity,
+    int slot_capacity) {
   __shared__ int32_t die[kOrderChunk];
+  __shared__ int32_t n_pieces[kOrderChunk];
   const int pos = blockIdx.x * kOrderChunk + threadIdx.x;
   const int row = pos < rows ? order_by_cost[pos] : -1;
   const int x = row >= 0 ? xcd_of_row(meta, row) : -1;
+  const int64_t split_len = split_length(sel_ptr[rows] - sel_ptr[0], slot_capacity);
+  const int64_t sel_begin = row >= 0 ? sel_ptr[row] : 0;
+  const int64_t n_sel = row >= 0 ? sel_ptr[row + 1] - sel_begin : 0;
+  const int pieces = pieces_of(n_sel, split_len);
   die[threadIdx.x] = x;
+  n_pieces[threadIdx.x] = pieces;
   __syncthreads();
   if (row < 0) return;
-  int rank = 0;
-  for (int t = 0; t < int(threadIdx.x); ++t) rank += die[t] == x;
-  order[queue_begin[x] + xcd_hist[blockIdx.x * kXcds + x] + rank] = row;
+  int before = 0;
+  for (int t = 0; t < int(threadIdx.x); ++t) before += die[t] == x ? n_pieces[t] : 0;
+  const int dst = queue_begin[x] + xcd_hist[blockIdx.x * kXcds + x] + before;
+  if (dst < 0 || dst + pieces > item_capacity) return;   // never taken (see split_length); keeps stores in bounds
+  int slot = -1;
+  if (pieces > 1) {
+    slot = int(atomicAdd(&split_count->n_slots, uint32_t(pieces)));
+    if (slot + pieces > slot_capacity) return;           // never taken either
+    const uint32_t e = atomicAdd(&split_count->n_rows, 1u);
+    if (e >= uint32_t(slot_capacity / 2 + 1)) return;
+    split_rows[e] = SplitRow{row, slot, pieces, 0};
+  }
+  for (int c = 0; c < pieces; ++c) {
+    const int64_t first = piece_begin(n_sel, pieces, c);
+    ItemRec rec;
+    rec.row = row;
+    rec.n_sel = int32_t(max(piece_begin(n_sel, pieces, c + 1) - first, int64_t(0)));
+    rec.sel_begin = sel_begin + first;
+    rec.slot = pieces > 1 ? slot + c : -1;
+    rec.reserved[0] = rec.reserved[1] = rec.reserved[2] = 0;
+    items[dst + c] = rec;
+  }
 }
 
 // Both sorts in one workgroup, for launches of few rows (prompts of a few thousand tokens, a
@@ -168,7 +209,7 @@ constexpr int kSmallKeys = 16384;     // LDS histogram entries: kXcds * (cost bi
 constexpr int kSmallRows = 16384;
 
 __global__ __launch_bounds__(kSmallThreads) void order_small_kernel(
-    SeqMeta meta, const int64_t* __restrict__ sel_ptr, int32_t* __restrict__ order,
+    SeqMeta meta, const int64_t* __restrict__ sel_ptr, ItemRec* __restrict__ items,
     int32_t* __restrict__ queue_begin, uint32_t* __restrict__ tickets, int rows, int n_bins) {
   __shared__ int32_t slot[kSmallKeys];               // count per key, then next free position per key
   __shared__ int32_t wave_sum[kSmallThreads / 64];
@@ -205,7 +246,15 @@ __global__ __launch_bounds__(kSmallThreads) void order_small_kernel(
   }
   if (tid == 0) queue_begin[kXcds] = rows;
   __syncthreads();
-  for (int row = tid; row < rows; row += kSmallThreads) order[atomicAdd(&slot[key_of(row)], 1)] = row;
+  for (int row = tid; row < rows; row += kSmallThreads) {
+    ItemRec rec;                                     // rows stay whole on this path
+    rec.row = row;
+    rec.sel_begin = sel_ptr[row];
+    rec.n_sel = int32_t(max(sel_ptr[row + 1] - rec.sel_begin, int64_t(0)));
+    rec.slot = -1;
+    rec.reserved[0] = rec.reserved[1] = rec.reserved[2] = 0;
+    items[atomicAdd(&slot[key_of(row)], 1)] = rec;
+  }
 }
 
 }  // namespace
@@ -218,12 +267,14 @@ int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceL
   int32_t* hist = reinterpret_cast<int32_t*>(workspace + w.hist);
   int32_t* bin_start = reinterpret_cast<int32_t*>(workspace + w.bin_start);
   int32_t* order_by_cost = reinterpret_cast<int32_t*>(workspace + w.order_by_cost);
-  int32_t* order = reinterpret_cast<int32_t*>(workspace + w.order);
+  ItemRec* items = reinterpret_cast<ItemRec*>(workspace + w.items);
+  SplitRow* split_rows = reinterpret_cast<SplitRow*>(workspace + w.split_rows);
+  SplitCounters* split_count = reinterpret_cast<SplitCounters*>(workspace + w.split_count);
   int32_t* xcd_hist = reinterpret_cast<int32_t*>(workspace + w.xcd_hist);
   int32_t* queue_begin = reinterpret_cast<int32_t*>(workspace + w.queue_begin);
   uint32_t* tickets = reinterpret_cast<uint32_t*>(workspace + w.tickets);
-  if (rows <= kSmallRows && kXcds * n_bins <= kSmallKeys) {
-    hipLaunchKernelGGL(order_small_kernel, dim3(1), dim3(kSmallThreads), 0, stream, g.meta, sel_ptr, order,
+  if (w.slot_capacity == 0 && rows <= kSmallRows && kXcds * n_bins <= kSmallKeys) {
+    hipLaunchKernelGGL(order_small_kernel, dim3(1), dim3(kSmallThreads), 0, stream, g.meta, sel_ptr, items,
                        queue_begin, tickets, rows, n_bins);
     if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
     return SHPLB_OK;
@@ -232,11 +283,12 @@ int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceL
                      rows, n_bins);
   hipLaunchKernelGGL(order_scan_kernel, dim3(1), dim3(1024), 0, stream, hist, bin_start, n_chunks, n_bins);
   hipLaunchKernelGGL(order_scatter_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, g.meta, sel_ptr, hist,
-                     bin_start, order_by_cost, xcd_hist, rows, n_bins);
+                     bin_start, order_by_cost, xcd_hist, rows, n_bins, int(w.slot_capacity));
   hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(64 * kXcds), 0, stream, xcd_hist, queue_begin, tickets,
-                     n_chunks);
-  hipLaunchKernelGGL(queue_scatter_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, g.meta, order_by_cost,
-                     xcd_hist, queue_begin, order, rows);
+                     split_count, n_chunks);
+  hipLaunchKernelGGL(queue_scatter_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, g.meta, sel_ptr,
+                     order_by_cost, xcd_hist, queue_begin, items, split_rows, split_count, rows,
+                     int(w.item_capacity), int(w.slot_capacity));
   if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
   return SHPLB_OK;
 }

@@ -12,6 +12,11 @@ constexpr int kCostBins = 4100;       // selected-block counts 0..SHPLB_MAX_BLOC
 constexpr int kOrderChunk = 256;      // rows per workgroup in the ordering kernels
 constexpr int kXcds = 8;              // accelerator dies (XCDs) of an MI355X, each with its own L2
 constexpr int kTicketStride = 16;     // uint32 slots between two queue tickets (one 64-byte line each)
+constexpr int kSplitSlotsMax = 1 << 16;   // most partial-result slots a caller may ask for (64 KB + 1 KB each)
+constexpr int kSplitMinBlocks = 16;   // a piece of a split row is never shorter than about this many key blocks
+constexpr int kSplitBlock = 128;      // rows are split only at this block size (the pipelined kernel)
+constexpr int64_t kSlotFloatsO = 128 * kHeadDim;   // one partial result: unnormalised O of 128 queries ...
+constexpr int64_t kSlotFloatsML = 2 * 128;         // ... and their reference exponent and denominator
 
 // Sequence geometry, passed to kernels by value (about 1 KB of kernel arguments).
 struct SeqMeta {
@@ -43,7 +48,12 @@ struct Geometry {
 struct WorkspaceLayout {
   int64_t qbar, kbar;        // pooled blocks as three bf16 planes, each [H][total_blocks][128]
   int64_t order_by_cost;     // int32 [rows]: rows by descending cost (intermediate)
-  int64_t order;             // int32 [rows]: the same, split into one queue per XCD
+  int64_t items;             // ItemRec [item_capacity]: the work items, one queue per XCD after the other
+  int64_t split_rows;        // SplitRow [slot_capacity / 2]: the rows that were split, in no particular order
+  int64_t split_count;       // SplitCounters
+  int64_t part_o;            // float [slot_capacity][128][kHeadDim]: partial results of the pieces
+  int64_t part_ml;           // float [slot_capacity][2][128]
+  int64_t item_capacity, slot_capacity;   // counts, not offsets
   int64_t hist;              // int32 [n_chunks][kCostBins]
   int64_t bin_start;         // int32 [kCostBins]
   int64_t xcd_hist;          // int32 [n_chunks][kXcds]
@@ -53,7 +63,8 @@ struct WorkspaceLayout {
 };
 
 int32_t make_geometry(const shplb_problem* p, Geometry* g);
-WorkspaceLayout make_layout(const Geometry& g);
+// split_slots: partial-result slots for rows split along the keys (0: rows stay whole)
+WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots = 0);
 int32_t persistent_workgroups();   // for the current device; <0 on HIP error
 
 // Kernel launchers (each returns a SHPLB status).
@@ -65,21 +76,70 @@ int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceL
                      char* workspace, hipStream_t stream);
 int32_t launch_mfma_rate(int random_operands, int iters, int n_workgroups, void* scratch, hipStream_t stream);
 int32_t launch_block_mass(const Geometry& g, const void* q, const void* k, float* mass, hipStream_t stream);
+// One work item of an attention launch: a row, or one piece of a row that was split along
+// its selected key blocks (positions [first, first + n_sel) of the row's selection).
+struct alignas(32) ItemRec {
+  int32_t row;
+  int32_t n_sel;        // selected key blocks this item covers
+  int64_t sel_begin;    // index of its first one in sel_idx
+  int32_t slot;         // partial-result slot it writes, or -1: the item is the whole row and writes the output
+  int32_t reserved[3];
+};
+
+// A row that was split: its pieces wrote partial results to slots [slot, slot + pieces).
+struct SplitRow {
+  int32_t row, slot, pieces, reserved;
+};
+
+struct SplitCounters {
+  uint32_t n_slots, n_rows;   // slots handed out, rows split (zeroed by the ordering kernels)
+};
+
+// Longest item, in key blocks, for a launch whose rows select total_cost blocks in all and
+// whose workspace has room for slot_capacity partial results (0: never split).  Rows longer
+// than this are cut into near-equal pieces so that no single item is a large part of a
+// workgroup's share (total / workgroups) and the launch ends evenly.  The length also bounds
+// the slots in use: a split row of n blocks has ceil(n / len) < 2 n / len pieces, so all
+// split rows together have fewer than 2 total / len <= slot_capacity.
+__host__ __device__ inline int64_t split_length(int64_t total_cost, int slot_capacity) {
+  if (slot_capacity < 2) return int64_t(1) << 40;
+  const int64_t len = (2 * total_cost + slot_capacity - 1) / slot_capacity;
+  return len < kSplitMinBlocks ? kSplitMinBlocks : len;
+}
+__host__ __device__ inline int pieces_of(int64_t n_sel, int64_t split_len) {
+  return n_sel > split_len ? int((n_sel + split_len - 1) / split_len) : 1;
+}
+// piece c of a row of n selected blocks cut into p pieces covers [piece_begin(c), piece_begin(c + 1))
+__host__ __device__ inline int64_t piece_begin(int64_t n_sel, int p, int c) { return n_sel * c / p; }
+
 // The per-XCD work queues the ordering kernels build (device pointers into the workspace).
 struct WorkQueues {
-  const int32_t* order;        // rows, queue after queue, each by descending cost
+  const ItemRec* items;        // items, queue after queue, each by descending row cost
   const int32_t* queue_begin;  // [kXcds + 1]
   uint32_t* tickets;           // [kXcds * kTicketStride], zeroed by the ordering kernels
 };
 
+// Where the pieces of split rows leave their results, and the list the merge runs over.
+struct SplitBuffers {
+  float* part_o;
+  float* part_ml;
+  const SplitRow* rows;
+  const SplitCounters* count;
+  int32_t slot_capacity;
+};
+
+// Combine the partial results of split rows into out and lse (merge_kernel.hip).
+int32_t launch_merge(const Geometry& g, SplitBuffers sb, void* out, float* lse, hipStream_t stream);
+
 int32_t launch_attention(const Geometry& g, const void* q, const void* k, const void* v,
                          const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                         shplb_wg_stats* stats, WorkQueues wq, int32_t n_wg, hipStream_t stream);
+                         shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg, hipStream_t stream);
 
 // Pipelined variant for 128-token blocks (attn_pipe_kernel.hip).
 void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
                               const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                              shplb_wg_stats* stats, WorkQueues wq, int32_t n_wg, hipStream_t stream);
+                              shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg,
+                              hipStream_t stream);
 
 // Row -> (sequence, head, query block).  Rows of one sequence are contiguous.
 __device__ __forceinline__ void decode_row(const SeqMeta& m, int32_t row, int& s, int& h, int& i, int& nb) {
@@ -131,7 +191,8 @@ __device__ __attribute__((noinline)) int fullest_queue(const int32_t* queue_begi
 // have work in proportion to what is left there, and no queue is left for last with its
 // heavy items still in it.  An old count only affects which queue is tried, the ticket
 // decides.  A queue whose ticket came back past its end is never tried again, so the loop
-// ends after at most kXcds misses.  Returns the row, or -1 when every queue is empty.
+// ends after at most kXcds misses.  Returns the item's position in wq.items, or -1 when
+// every queue is empty.
 __device__ __forceinline__ int32_t next_item(const WorkQueues& wq, int home, int& empty_mask) {
   int pick = home;
   for (;;) {
@@ -141,7 +202,7 @@ __device__ __forceinline__ int32_t next_item(const WorkQueues& wq, int home, int
     }
     const int begin = wq.queue_begin[pick], end = wq.queue_begin[pick + 1];
     const uint32_t t = atomicAdd(wq.tickets + pick * kTicketStride, 1u);
-    if (t < uint32_t(end - begin)) return wq.order[begin + int(t)];
+    if (t < uint32_t(end - begin)) return begin + int(t);
     empty_mask |= 1 << pick;
   }
 }

@@ -56,6 +56,16 @@ class GpuRun:
                                     self.sel_idx if sel_idx is None else sel_idx,
                                     self.out, self.lse, self.stats, self.ws, torch.cuda.current_stream())
 
+    def attn_split_step(self, split_slots):
+        """The attention step with long rows cut into pieces (own, larger workspace)."""
+        if getattr(self, "split_slots", None) != split_slots:
+            self.split_slots = split_slots
+            self.ws_split = torch.empty(S.shplb_split_workspace_bytes(self.p, split_slots), dtype=torch.uint8,
+                                        device="cuda:0")
+        S.shplb_sparse_attn_prefill_split(self.p, self.q, self.k, self.v, self.sel_ptr, self.sel_idx, self.out,
+                                          self.lse, self.stats, self.ws_split, split_slots,
+                                          torch.cuda.current_stream())
+
     def mass_step(self):
         """Offline recovery profile into its own buffer (same layout as the scores)."""
         if not hasattr(self, "mass"):

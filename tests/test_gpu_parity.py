@@ -90,6 +90,39 @@ def test_long_and_short_rows_mixed():
     assert st["n_items"].sum() == run.rows
 
 
+@pytest.mark.parametrize("split_slots", [256, 1024])
+def test_long_rows_split_along_keys_and_merged(split_slots):
+    # shplb_sparse_attn_prefill_split on the same mixed case: with 1024 slots every row of more
+    # than 16 selected blocks is cut into pieces, with 256 slots only those of more than 22 are (the cut
+    # length rises so that the pieces fit the slots).  Compared with the oracle like the plain
+    # entry point, and with the plain entry point's own output.
+    wl = make_custom([128 * 40 + 37, 128 * 11], 4, 2, 128, [999, 999, 23, 3, 999, 18, 2, 7], seed=61, name="split")
+    run = _gpu()(wl).run_all()
+    o_plain, l_plain = run.out.clone(), run.lse.clone()
+    run.out.zero_(); run.lse.zero_()
+    run.attn_split_step(split_slots)
+    torch.cuda.synchronize()
+    sc_o = orc.block_scores(wl.q, wl.k, wl.cu_seqlens, wl.block, None)
+    ptr_o, _ = orc.select_blocks(sc_o, wl.budgets)
+    out_o, lse_o = orc.sparse_attention(wl.q, wl.k, wl.v, wl.cu_seqlens, wl.block, ptr_o, run.sel_idx_host(), None, None)
+    wa, wr = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
+    st = run.stats_host()
+    print("  split_slots %d: items %d for %d rows, out max abs %.3g max rel %.3g" % (
+        split_slots, st["n_items"].sum(), run.rows, wa, wr), flush=True)
+    assert st["cost_blocks"].sum() == run.sel_ptr_host[-1]      # every selected block visited exactly once
+    assert st["n_items"].sum() > run.rows                       # more items than rows: pieces
+    # against the unsplit result: the same sums in another order
+    d = (run.out.float() - o_plain.float()).abs().max().item()
+    assert d <= 2.0 ** -6, d
+    assert (run.lse - l_plain).abs().max().item() <= 2e-3       # denominators are sums of bf16-rounded probabilities
+    o1, l1 = run.out.clone(), run.lse.clone()
+    run.out.zero_(); run.lse.zero_()
+    run.attn_split_step(split_slots)
+    torch.cuda.synchronize()
+    assert torch.equal(run.out.view(torch.int16), o1.view(torch.int16))   # slot numbering does not matter
+    assert torch.equal(run.lse, l1)
+
+
 def test_explicit_softmax_scale():
     wl = make_custom([700], 2, 2, 64, [3, 6], seed=41, name="scale")
     full_parity(wl, softmax_scale=0.05)
