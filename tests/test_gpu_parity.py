@@ -123,6 +123,43 @@ def test_long_rows_split_along_keys_and_merged(split_slots):
     assert torch.equal(run.lse, l1)
 
 
+@pytest.mark.parametrize("block", [64, 128])
+def test_packed_qkv_strides(block):
+    # Q, K, V as column slices of one [T, Hq + 2 Hkv, 128] buffer (the output of a fused QKV
+    # projection), O into a buffer with the strides of Q: only the addressing differs from the
+    # contiguous case, so scores, selection, output and lse must come out bit-identical to it,
+    # and the contiguous case is what the oracle checks.
+    import paper_2603_10353_amd as S
+    from harness import to_dev_bf16
+    wl = make_custom([128 * 9 + 77, 300], 6, 2, block, [5, 999, 3, 7, 2, 4] * 2, seed=71, name="packed")
+    ref = full_parity(wl)
+    hq, hkv, d = wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    width = hq + 2 * hkv
+    packed = torch.empty((ref.q.shape[0], width, d), dtype=torch.bfloat16, device="cuda:0")
+    packed[:, :hq] = to_dev_bf16(wl.q)
+    packed[:, hq:hq + hkv] = to_dev_bf16(wl.k)
+    packed[:, hq + hkv:] = to_dev_bf16(wl.v)
+    q, k, v = packed[:, :hq], packed[:, hq:hq + hkv], packed[:, hq + hkv:]
+    out_buf = torch.zeros_like(packed)
+    out = out_buf[:, :hq]
+    p = S.Problem(wl.cu_seqlens, hq, hkv, block, d, q_stride_t=width * d, q_stride_h=d,
+                  kv_stride_t=width * d, kv_stride_h=d)
+    ws = torch.empty(S.shplb_workspace_bytes(p), dtype=torch.uint8, device="cuda:0")
+    scores = torch.full_like(ref.scores, float("nan"))
+    sel_idx = torch.full_like(ref.sel_idx, -1)
+    lse = torch.zeros_like(ref.lse)
+    st = torch.cuda.current_stream()
+    S.shplb_block_scores(p, q, k, scores, ws, st)
+    S.shplb_select_topk_per_head(p, scores, wl.budgets, ref.sel_ptr, sel_idx, st)
+    S.shplb_sparse_attn_prefill(p, q, k, v, ref.sel_ptr, sel_idx, out, lse, None, ws, st)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.nan_to_num(scores, nan=-7.0), torch.nan_to_num(ref.scores, nan=-7.0))
+    assert torch.equal(sel_idx, ref.sel_idx)
+    assert torch.equal(out.contiguous().view(torch.int16), ref.out.view(torch.int16))
+    assert torch.equal(lse, ref.lse)
+    assert not out_buf[:, hq:].any()                    # nothing written outside the O columns
+
+
 def test_explicit_softmax_scale():
     wl = make_custom([700], 2, 2, 64, [3, 6], seed=41, name="scale")
     full_parity(wl, softmax_scale=0.05)
