@@ -133,8 +133,9 @@ SHPLB_API int32_t shplb_select_topk_per_head(const shplb_problem* p, const float
  * token-level causal mask inside the diagonal block), bf16 MFMA with fp32
  * accumulation and fp32 online softmax.  Work items are the rows; they are
  * ordered by descending selected-block count and handed to persistent
- * workgroups through one device counter: the greedy rule of Section 3.3 (largest
- * first, to whichever worker is free first) applied to compute units.
+ * workgroups through one queue per accelerator die with an atomic ticket each:
+ * the greedy rule of Section 3.3 (largest first, to whichever worker is free
+ * first) applied to compute units.
  *   sel_ptr/sel_idx: device CSR; every row's list must be ascending, within
  *   [0, i], and contain i (lists written by shplb_select_topk_per_head are).
  *   out: device bf16 [T, n_q_heads, head_dim], strides as Q.

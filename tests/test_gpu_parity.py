@@ -160,6 +160,31 @@ def test_packed_qkv_strides(block):
     assert not out_buf[:, hq:].any()                    # nothing written outside the O columns
 
 
+@pytest.mark.parametrize("block", [64, 128])
+def test_caller_supplied_selection_sink_and_window(block):
+    # The attention step on a selection that did not come from the selection kernel: every row
+    # keeps block 0 and a window of its last w_h blocks (ascending, contains the diagonal), the
+    # window differing per head; the first rows have a single block.  Ragged tail, two sequences.
+    wl = make_custom([block * 21 + 13, block * 2 + 1], 4, 2, block, [2] * 8, seed=81, name="window")
+    run = _gpu()(wl)
+    windows = [1, 2, 5, 30]
+    ptr, idx = [0], []
+    for s, nb in enumerate(wl.n_blocks):
+        for h in range(wl.n_q_heads):
+            for i in range(nb):
+                sel = sorted({0} | set(range(max(0, i - windows[h] + 1), i + 1)))
+                idx += sel
+                ptr.append(len(idx))
+    ptr, idx = np.asarray(ptr, np.int64), np.asarray(idx, np.int32)
+    run.attn_step(torch.from_numpy(ptr).to("cuda:0"), torch.from_numpy(idx).to("cuda:0"))
+    torch.cuda.synchronize()
+    out_o, lse_o = orc.sparse_attention(wl.q, wl.k, wl.v, wl.cu_seqlens, wl.block, ptr, idx, None, None)
+    wa, wr = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
+    st = run.stats_host()
+    assert st["cost_blocks"].sum() == len(idx) and st["n_items"].sum() == run.rows
+    print("  window selection: out max abs %.3g max rel %.3g" % (wa, wr), flush=True)
+
+
 def test_explicit_softmax_scale():
     wl = make_custom([700], 2, 2, 64, [3, 6], seed=41, name="scale")
     full_parity(wl, softmax_scale=0.05)
