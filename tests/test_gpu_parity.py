@@ -185,6 +185,36 @@ def test_caller_supplied_selection_sink_and_window(block):
     print("  window selection: out max abs %.3g max rel %.3g" % (wa, wr), flush=True)
 
 
+def test_whole_path_in_a_hip_graph():
+    # The three entry points captured into one HIP graph (kernel launches only, no memset nodes: the
+    # ordering kernels clear their own counters) and replayed several times with eager work
+    # and synchronisations in between; every replay must reproduce the eager result bit for bit.
+    wl = make_workload(1, seqlens=[128 * 37 + 5])
+    run = _gpu()(wl).run_all()                       # eager pass: reference, and warms up every lazy init
+    ref = (run.scores.clone(), run.sel_idx.clone(), run.out.clone(), run.lse.clone())
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run.scores_step(); run.select_step(); run.attn_step()      # once on the side stream before capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run.scores_step()
+            run.select_step()
+            run.attn_step()
+    torch.cuda.synchronize()
+    for replay in range(4):
+        run.scores.fill_(float("nan")); run.sel_idx.fill_(-1); run.out.zero_(); run.lse.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        nan = lambda t: torch.nan_to_num(t, nan=-7.0)
+        assert torch.equal(nan(run.scores), nan(ref[0])), replay
+        assert torch.equal(run.sel_idx, ref[1]), replay
+        assert torch.equal(run.out.view(torch.int16), ref[2].view(torch.int16)), replay
+        assert torch.equal(run.lse, ref[3]), replay
+
+
 def test_explicit_softmax_scale():
     wl = make_custom([700], 2, 2, 64, [3, 6], seed=41, name="scale")
     full_parity(wl, softmax_scale=0.05)
