@@ -57,7 +57,7 @@ struct WorkspaceLayout {
   int64_t hist;              // int32 [n_chunks][kCostBins]
   int64_t bin_start;         // int32 [kCostBins]
   int64_t xcd_hist;          // int32 [n_chunks][kXcds]
-  int64_t queue_begin;       // int32 [kXcds + 1]: queue x is order[queue_begin[x] .. queue_begin[x+1])
+  int64_t queue_begin;       // int32 [kXcds + 1]: queue x is items[queue_begin[x] .. queue_begin[x+1])
   int64_t tickets;           // uint32 [kXcds * kTicketStride]
   int64_t total;
 };
