@@ -17,9 +17,10 @@ __device__ __forceinline__ int popc64(uint64_t m) { return __builtin_popcountll(
 //
 // The row keeps block 0 and block i, then the `want` best of the candidates 1..i-1
 // under the total order (score descending, index ascending).  The wave finds the
-// want-th largest key t by a 32-step bitwise search (largest t with
-// count(key >= t) >= want), takes every key > t, and fills the remainder with the
-// lowest-index keys equal to t.  Output is written in ascending block order.
+// want-th largest key t by a bitwise search (largest t with count(key >= t) >= want;
+// at most 32 steps, usually about a dozen), takes every key > t, and fills the
+// remainder with the lowest-index keys equal to t.  Output is written in ascending
+// block order.
 template <int SLOTS>
 __global__ __launch_bounds__(256) void select_kernel(
     SeqMeta meta, const float* __restrict__ scores, const int64_t* __restrict__ sel_ptr,
@@ -61,14 +62,39 @@ __global__ __launch_bounds__(256) void select_kernel(
     return;
   }
 
-  uint32_t t = 0;
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t probe = t | (1u << bit);
-    int cnt = 0;
+  // All candidates lie between the smallest and the largest key, so t shares their common
+  // leading bits (for scores of one sign and similar magnitude: sign and most of the
+  // exponent); the search starts below them.  It ends early when a probe splits off exactly
+  // `want` keys: those are the selection, whatever the lower bits of t would be.
+  uint32_t kmax = 0, kmin = 0xffffffffu;
 #pragma unroll
-    for (int c = 0; c < SLOTS; ++c)
-      if (c < slots) cnt += popc64(__ballot(key[c] >= probe));
-    if (cnt >= want) t = probe;
+  for (int c = 0; c < SLOTS; ++c)
+    if (c < slots && key[c] != 0) {
+      kmax = max(kmax, key[c]);
+      kmin = min(kmin, key[c]);
+    }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    kmax = max(kmax, uint32_t(__shfl_xor(int(kmax), d)));
+    kmin = min(kmin, uint32_t(__shfl_xor(int(kmin), d)));
+  }
+  const uint32_t differ = kmax ^ kmin;
+  uint32_t t = kmax;                            // all candidates equal: ties only
+  if (differ != 0) {
+    const int top = 31 - __builtin_clz(differ);  // highest bit in which two candidates differ
+    t = top == 31 ? 0u : kmax & ~((2u << top) - 1u);
+    for (int bit = top; bit >= 0; --bit) {
+      const uint32_t probe = t | (1u << bit);
+      int cnt = 0;
+#pragma unroll
+      for (int c = 0; c < SLOTS; ++c)
+        if (c < slots) cnt += popc64(__ballot(key[c] >= probe));
+      if (cnt == want) {
+        t = probe - 1;                          // keys > t are exactly the `want` keys >= probe
+        break;
+      }
+      if (cnt > want) t = probe;
+    }
   }
   int above = 0;
 #pragma unroll
