@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM traffic of one attention launch measured with rocprofv3 --pmc (FETCH_SIZE, then
 # WRITE_SIZE), scaled by a copy kernel of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg2_llama3_8b_128k": 2 * 11652460.2 * 1024 + 1070218.2 * 1024}
+MEASURED_TRAFFIC_BYTES = {"cfg2_llama3_8b_128k": 2 * 13371986.6 * 1024 + 1072592.9 * 1024}
 
 
 def selected_pairs(cu_seqlens, block, n_q_heads, sel_ptr_host):

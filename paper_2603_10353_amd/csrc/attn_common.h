@@ -29,11 +29,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 
 // Chunk swizzle of row r (only r mod 16 matters): a bijection on the 16 chunk slots.
-// Low three row bits move a chunk by pairs of slots (what the transpose reads of V
-// need: four consecutive key rows land in four different 32-byte bank groups), bit 3
-// of the row flips the slot inside the pair (sixteen consecutive K rows read by the
-// lanes of one operand fetch cover all sixteen slots).
-__device__ __forceinline__ int swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
+// The two low row bits move a chunk by 64 bytes, bit 2 by 32 bytes, bit 3 by 16 bytes.
+// A transpose read of V serves 32 lanes per cycle: four consecutive key rows, 64 bytes
+// of each; with this they fall on the four different 64-byte quarters of the 64 banks
+// (SQ_LDS_BANK_CONFLICT reads zero; with rows only 32 bytes apart every such read took
+// twice as long).  Sixteen consecutive K rows read by the lanes of one operand fetch
+// cover all sixteen slots under any bijection.
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1); }
 
 // LDS transpose read: inside every group of 16 lanes, lane L receives element L%4 of
 // the four 8-byte pieces addressed by lanes L/4, L/4+4, L/4+8, L/4+12.
