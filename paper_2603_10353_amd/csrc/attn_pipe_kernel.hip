@@ -183,14 +183,16 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     auto mask_scores = [&](f32x16 (&sc)[2][NT], int t) {          // diagonal block: keys above the query
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        const int q_in = wave * QW + 32 * nt + n;
+        // key position minus query position, up to the part that depends on the register: taken
+        // through an opaque move so that the 32 comparisons are made here, on the rare diagonal
+        // tile, instead of being hoisted out of the item loop into 64 scalar registers of masks
+        int d = kKeysPerTile * (t & 1) + 4 * hi - (wave * QW + 32 * nt + n);
+        asm volatile("" : "+v"(d));
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key_in = kKeysPerTile * (t & 1) + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
-            if (key_in > q_in) sc[mt][nt][r] = -INFINITY;
-          }
+          for (int r = 0; r < 16; ++r)
+            if (d + (32 * mt + 8 * (r >> 2) + (r & 3)) > 0) sc[mt][nt][r] = -INFINITY;
       }
     };
     // mx[nt] = in-lane maximum of a tile's scores: raise the reference to it where it is higher
