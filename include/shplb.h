@@ -50,11 +50,12 @@ extern "C" {
 #define SHPLB_E_SHAPE       (-2)  /* bad shape, stride, alignment or cu_seqlens */
 #define SHPLB_E_BUDGET      (-3)  /* negative budget, or partition cannot hold the units */
 #define SHPLB_E_WORKSPACE   (-4)  /* reserved: workspace too small */
-#define SHPLB_E_UNSUPPORTED (-5)  /* head_dim != 128, block not 64/128, too many sequences/blocks */
+#define SHPLB_E_UNSUPPORTED (-5)  /* head_dim != 128, block not 64/128, too many sequences/blocks/heads */
 #define SHPLB_E_HIP         (-6)  /* a HIP call or kernel launch failed */
 
 #define SHPLB_MAX_SEQ        64    /* sequences per call */
 #define SHPLB_MAX_BLOCKS   4096    /* blocks per sequence */
+#define SHPLB_MAX_SEQ_HEADS 65535  /* n_seq * n_q_heads per call */
 
 typedef struct {
   int32_t n_seq;                 /* 1..SHPLB_MAX_SEQ */
@@ -81,6 +82,10 @@ typedef struct {
 
 /* Number of (sequence, head, query block) rows. */
 SHPLB_API int32_t shplb_num_rows(const shplb_problem* p, int64_t* rows_out /*host*/);
+
+/* Largest block count of any sequence, max_s nb_s (shplb_recovery_curves takes
+ * n_levels = this + 1). */
+SHPLB_API int32_t shplb_max_blocks(const shplb_problem* p, int32_t* max_nb_out /*host*/);
 
 /* Bytes of device workspace any entry point below needs for this problem. */
 SHPLB_API int32_t shplb_workspace_bytes(const shplb_problem* p, int64_t* bytes_out /*host*/);

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     shplb_balance_heads,
     shplb_block_mass,
     shplb_block_scores,
+    shplb_max_blocks,
     shplb_num_rows,
     shplb_probe_mfma_rate,
     shplb_recovery_curves,

@@ -11,7 +11,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = [
-    "shplb_num_rows", "shplb_workspace_bytes", "shplb_score_layout", "shplb_sel_row_ptr",
+    "shplb_num_rows", "shplb_max_blocks", "shplb_workspace_bytes", "shplb_score_layout", "shplb_sel_row_ptr",
     "shplb_sched_num_workgroups", "shplb_block_scores", "shplb_select_topk_per_head",
     "shplb_sparse_attn_prefill", "shplb_split_workspace_bytes", "shplb_sparse_attn_prefill_split",
     "shplb_balance_heads", "shplb_shift_budgets", "shplb_block_mass",
@@ -75,6 +75,7 @@ def load_library():
     i32, i64, vp = C.c_int32, C.c_int64, C.c_void_p
     pp = C.POINTER(_CProblem)
     lib.shplb_num_rows.argtypes = [pp, C.POINTER(i64)]
+    lib.shplb_max_blocks.argtypes = [pp, C.POINTER(i32)]
     lib.shplb_workspace_bytes.argtypes = [pp, C.POINTER(i64)]
     lib.shplb_score_layout.argtypes = [pp, C.POINTER(i64)]
     lib.shplb_sel_row_ptr.argtypes = [pp, C.POINTER(i32), C.POINTER(i64)]
@@ -155,6 +156,12 @@ def shplb_strerror(status: int) -> str:
 def shplb_num_rows(p: Problem) -> int:
     out = C.c_int64()
     _check(load_library().shplb_num_rows(p.ref(), C.byref(out)), "shplb_num_rows")
+    return out.value
+
+
+def shplb_max_blocks(p: Problem) -> int:
+    out = C.c_int32()
+    _check(load_library().shplb_max_blocks(p.ref(), C.byref(out)), "shplb_max_blocks")
     return out.value
 
 
@@ -263,8 +270,7 @@ def shplb_recovery_curves(p: Problem, mass_host) -> np.ndarray:
     off = shplb_score_layout(p)
     if m.size != int(off[-1]):
         raise ValueError("mass has %d floats, layout needs %d" % (m.size, int(off[-1])))
-    nbs = [-(-(int(p.cu[s + 1]) - int(p.cu[s])) // p.c.block) for s in range(len(p.cu) - 1)]
-    n_levels = max(nbs) + 1
+    n_levels = shplb_max_blocks(p) + 1
     curves = np.zeros((p.c.n_q_heads, n_levels), np.float64)
     _check(load_library().shplb_recovery_curves(p.ref(), m.ctypes.data_as(C.POINTER(C.c_float)), n_levels,
                                                 curves.ctypes.data_as(C.POINTER(C.c_double))),

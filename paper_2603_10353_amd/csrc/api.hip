@@ -17,6 +17,8 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g) {
   if (!p || !p->cu_seqlens) return SHPLB_E_NULL;
   if (p->n_seq < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1) return SHPLB_E_SHAPE;
   if (p->n_seq > SHPLB_MAX_SEQ) return SHPLB_E_UNSUPPORTED;
+  // (sequence, head) pairs index the z dimension of the scoring grid
+  if (int64_t(p->n_seq) * p->n_q_heads > SHPLB_MAX_SEQ_HEADS) return SHPLB_E_UNSUPPORTED;
   if (p->n_q_heads % p->n_kv_heads) return SHPLB_E_SHAPE;
   if (p->head_dim != kHeadDim) return SHPLB_E_UNSUPPORTED;
   if (p->block != 64 && p->block != 128) return SHPLB_E_UNSUPPORTED;
@@ -110,6 +112,14 @@ int32_t shplb_num_rows(const shplb_problem* p, int64_t* rows_out) {
   Geometry g;
   if (int32_t st = make_geometry(p, &g)) return st;
   *rows_out = g.rows;
+  return SHPLB_OK;
+}
+
+int32_t shplb_max_blocks(const shplb_problem* p, int32_t* max_nb_out) {
+  if (!max_nb_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  *max_nb_out = g.max_nb;
   return SHPLB_OK;
 }
 
@@ -245,8 +255,7 @@ int32_t shplb_sparse_attn_prefill_split(const shplb_problem* p, const void* q, c
                          stream);
 }
 
-// Greedy multiway partition of Section 3.3.  n is a head (or KV-group) count, so
-// the O(n * n_parts) scan for the least-loaded part is as good as a heap here.
+// Offline recovery profile of Section 2.4 at block granularity: a dense causal pass.
 int32_t shplb_block_mass(const shplb_problem* p, const void* q, const void* k, float* mass_out, void* stream) {
   if (!q || !k || !mass_out) return SHPLB_E_NULL;
   Geometry g;
@@ -285,6 +294,8 @@ int32_t shplb_recovery_curves(const shplb_problem* p, const float* mass, int32_t
   return SHPLB_OK;
 }
 
+// Greedy multiway partition of Section 3.3.  n is a head (or KV-group) count, so
+// the O(n * n_parts) scan for the least-loaded part is as good as a heap here.
 int32_t shplb_balance_heads(const int64_t* costs, int32_t n, int32_t n_parts,
                             int32_t max_per_part, int32_t* part_of_out, int64_t* loads_out) {
   if (n < 0 || n_parts < 1 || max_per_part < 0) return SHPLB_E_SHAPE;

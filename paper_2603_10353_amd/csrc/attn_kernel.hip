@@ -83,6 +83,7 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     __syncthreads();
     if (pos < 0) break;
     const int row = __builtin_amdgcn_readfirstlane(wq.items[pos].row);   // rows are never split at this block size
+    if (row < 0 || row >= meta.blk_begin[meta.n_seq] * meta.n_q_heads) continue;   // malformed item record
     int s, h, i, nb;
     decode_row(meta, row, s, h, i, nb);
     const int g = h / group;

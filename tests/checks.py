@@ -37,7 +37,8 @@ def compare_selection(ptr, idx_gpu, idx_orc, scores_orc_rows, row_meta):
 
 def compare_output(out_gpu, out_orc, lse_gpu=None, lse_orc=None, tokens=None):
     """out_*: [T, H, D] fp64 (NaN in the oracle = row not computed).  Per head:
-    max-abs <= OUT_MAX_ABS and max-abs / max|oracle| <= OUT_MAX_REL."""
+    max-abs <= OUT_MAX_ABS and max-abs / max|oracle| <= OUT_MAX_REL; lse within LSE_ATOL.
+    Returns the worst errors seen: (output max-abs, output max-rel, lse max-abs)."""
     mask = ~np.isnan(out_orc)
     assert mask.any()
     worst_abs = worst_rel = 0.0
@@ -51,8 +52,9 @@ def compare_output(out_gpu, out_orc, lse_gpu=None, lse_orc=None, tokens=None):
         worst_rel = max(worst_rel, d / ref)
         assert d <= OUT_MAX_ABS, "head %d: max abs err %.4g" % (h, d)
         assert d / ref <= OUT_MAX_REL, "head %d: max rel err %.4g (abs %.4g / ref %.4g)" % (h, d / ref, d, ref)
+    worst_lse = 0.0
     if lse_gpu is not None:
         lm = ~np.isnan(lse_orc)
-        dl = np.abs(lse_gpu[lm] - lse_orc[lm]).max()
-        assert dl <= LSE_ATOL, "lse max abs err %.4g" % dl
-    return worst_abs, worst_rel
+        worst_lse = float(np.abs(lse_gpu[lm] - lse_orc[lm]).max())
+        assert worst_lse <= LSE_ATOL, "lse max abs err %.4g" % worst_lse
+    return worst_abs, worst_rel, worst_lse

@@ -41,40 +41,103 @@ def _run_case(wl, n_sample, seed):
     rng = np.random.default_rng(seed)
     rows = set(np.argsort(-counts, kind="stable")[:4].tolist())          # the costliest rows
     rows |= set(np.argsort(counts, kind="stable")[:2].tolist())          # and the cheapest
-    rows |= set(rng.choice(len(counts), size=n_sample, replace=False).tolist())
+    first = 0
+    for nb in wl.n_blocks:                                               # the costliest and the last row of every sequence
+        seq_rows = np.arange(first, first + nb * wl.n_q_heads)
+        rows.add(int(seq_rows[np.argmax(counts[seq_rows])]))
+        rows.add(int(seq_rows[-1]))
+        first += nb * wl.n_q_heads
+    rows |= set(rng.choice(len(counts), size=min(n_sample, len(counts)), replace=False).tolist())
     out_o, lse_o = orc.sparse_attention(wl.q, wl.k, wl.v, wl.cu_seqlens, wl.block, ptr_o, idx_g, None, rows)
     out_g, lse_g = run.out_host(), run.lse_host()
-    wa, wr = compare_output(out_g, out_o, lse_g, lse_o)
+    wa, wr, wlse = compare_output(out_g, out_o, lse_g, lse_o)
     assert np.isfinite(out_g).all() and np.isfinite(lse_g).all()
     st = run.stats_host()
     assert st["n_items"].sum() == run.rows and st["cost_blocks"].sum() == ptr_o[-1]
     busy = (st["t_last"] - st["t_first"]).astype(np.float64)
     imb = busy.max() / busy.mean() - 1.0
-    print("  rows %d, waived %d, sampled %d rows: max abs %.3g max rel %.3g; busy-time imbalance %.3f%%"
-          % (len(counts), waived, len(rows), wa, wr, 100 * imb), flush=True)
+    print("  rows %d, waived %d, sampled %d rows: max abs %.3g max rel %.3g lse %.3g; busy-time imbalance %.3f%%"
+          % (len(counts), waived, len(rows), wa, wr, wlse, 100 * imb), flush=True)
     return run, imb
+
+
+def _constant_value_pass(run):
+    """The attention step again with every value row of a KV head replaced by one vector w_g.
+    Eq. 1 then gives O[t, h, :] = w_{g(h)} for every query, whatever was selected: a check of
+    the normalisation (weights over the selected keys sum to one) and of where each result
+    is written, on EVERY row of the output.  fp32 sums of p * w divided by the fp32 sum of
+    the same p, then one bf16 rounding: within one bf16 step of w (2^-8 relative), plus the
+    fp32 summation error, for which another half step is allowed.  The denominators do not
+    depend on V, so lse must repeat the first pass bit for bit."""
+    wl = run.wl
+    rng = np.random.default_rng(99)
+    w = torch.from_numpy(rng.uniform(0.5, 2.0, size=(wl.n_kv_heads, wl.head_dim)).astype(np.float32))
+    w = (w * torch.from_numpy(rng.choice([-1.0, 1.0], size=tuple(w.shape)).astype(np.float32))).to(torch.bfloat16)
+    lse_first = run.lse.clone()
+    run.v[:] = w.to(run.v.device)[None]
+    run.out.zero_()
+    run.lse.zero_()
+    run.attn_step()
+    torch.cuda.synchronize()
+    g = wl.n_q_heads // wl.n_kv_heads
+    want = w.to(run.out.device).float().repeat_interleave(g, 0)[None]           # [1, Hq, D]
+    worst = 0.0
+    for t0 in range(0, run.out.shape[0], 16384):
+        rel = ((run.out[t0:t0 + 16384].float() - want).abs() / want.abs()).max().item()
+        worst = max(worst, rel)
+    print("  constant value rows: every output row, worst relative deviation %.3g" % worst, flush=True)
+    assert worst <= 1.5 * 2.0 ** -8, worst
+    assert torch.equal(run.lse, lse_first)
 
 
 def test_config1_32k_full():
     run, imb = _run_case(make_workload(1), 48, seed=1)
     assert imb < 0.05
+    _constant_value_pass(run)
 
 
 def test_config2_128k_full():
     run, imb = _run_case(make_workload(2), 24, seed=2)
     assert imb < 0.05
+    _constant_value_pass(run)
 
 
 def test_config3_one_partition_share_64k():
     import paper_2603_10353_amd as S
     import bench
     heads, loads = bench.pick_config3_heads(S)
-    _run_case(make_workload(3, q_heads=heads), 32, seed=3)
+    run, imb = _run_case(make_workload(3, q_heads=heads), 32, seed=3)
+    # 8 heads, 4096 rows on 512 workgroups: eight items per workgroup, the coarsest case of the set
+    assert imb < 0.08
 
 
 def test_config4_varlen_batch_quarter_scale():
     # the 8K+24K+64K+128K batch at a quarter of its lengths (ragged by one token each), one launch
     _run_case(make_workload(4, seqlens=[2048 + 1, 6144 - 1, 16384 + 63, 32768 - 65]), 48, seed=4)
+
+
+def test_config4_varlen_batch_full():
+    # 8K + 24K + 64K + 128K tokens in one launch: 57 344 rows of four sequences go through the
+    # five-launch ordering (two counting sorts with multi-sequence row decoding) into one
+    # persistent attention launch.  Scores and selections on every row; attention on sampled
+    # rows that include the costliest and the last row of every sequence; then every output row
+    # through the constant-value check.
+    run, imb = _run_case(make_workload(4), 48, seed=5)
+    assert imb < 0.05
+    _constant_value_pass(run)
+
+
+def test_three_sequences_above_the_single_workgroup_ordering():
+    # 17 024 rows (> 16 384, where the single-workgroup ordering ends) from three ragged sequences
+    # of a 64/16-head layer: the five-launch ordering with multi-sequence decoding at a size where
+    # the sample can be dense (1 row in 70) and the oracle still finishes in seconds.
+    from workloads import make_custom
+    rng = np.random.default_rng(123)
+    budgets = rng.choice([2, 3, 5, 9, 17, 40, 999], size=3 * 64)
+    wl = make_custom([128 * 120 + 17, 128 * 90 - 5, 128 * 54 + 1], 64, 16, 128, budgets, seed=79, name="three_seq")
+    run, imb = _run_case(wl, 240, seed=6)
+    assert run.rows > 16384
+    _constant_value_pass(run)
 
 
 def test_max_blocks_per_sequence():

@@ -42,8 +42,9 @@ def full_parity(wl, softmax_scale=0.0, rows=None):
     waived = compare_selection(ptr_o, idx_g, idx_o, srow,
                                lambda r: orc.row_decode(wl.cu_seqlens, wl.block, wl.n_q_heads, r))
     out_o, lse_o = orc.sparse_attention(wl.q, wl.k, wl.v, wl.cu_seqlens, wl.block, ptr_o, idx_g, scale, rows)
-    wa, wr = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
-    print("  waived rows %d / %d, out max abs %.3g max rel %.3g" % (waived, len(ptr_o) - 1, wa, wr), flush=True)
+    wa, wr, wl_ = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
+    print("  waived rows %d / %d, out max abs %.3g max rel %.3g, lse max abs %.3g" % (waived, len(ptr_o) - 1, wa, wr, wl_),
+          flush=True)
     return run
 
 
@@ -105,7 +106,7 @@ def test_long_rows_split_along_keys_and_merged(split_slots):
     sc_o = orc.block_scores(wl.q, wl.k, wl.cu_seqlens, wl.block, None)
     ptr_o, _ = orc.select_blocks(sc_o, wl.budgets)
     out_o, lse_o = orc.sparse_attention(wl.q, wl.k, wl.v, wl.cu_seqlens, wl.block, ptr_o, run.sel_idx_host(), None, None)
-    wa, wr = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
+    wa, wr, wl_ = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
     st = run.stats_host()
     print("  split_slots %d: items %d for %d rows, out max abs %.3g max rel %.3g" % (
         split_slots, st["n_items"].sum(), run.rows, wa, wr), flush=True)
@@ -179,7 +180,7 @@ def test_caller_supplied_selection_sink_and_window(block):
     run.attn_step(torch.from_numpy(ptr).to("cuda:0"), torch.from_numpy(idx).to("cuda:0"))
     torch.cuda.synchronize()
     out_o, lse_o = orc.sparse_attention(wl.q, wl.k, wl.v, wl.cu_seqlens, wl.block, ptr, idx, None, None)
-    wa, wr = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
+    wa, wr, wl_ = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
     st = run.stats_host()
     assert st["cost_blocks"].sum() == len(idx) and st["n_items"].sum() == run.rows
     print("  window selection: out max abs %.3g max rel %.3g" % (wa, wr), flush=True)
