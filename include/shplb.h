@@ -49,7 +49,7 @@ extern "C" {
 #define SHPLB_E_NULL        (-1)  /* a required pointer is NULL */
 #define SHPLB_E_SHAPE       (-2)  /* bad shape, stride, alignment or cu_seqlens */
 #define SHPLB_E_BUDGET      (-3)  /* negative budget, or partition cannot hold the units */
-#define SHPLB_E_WORKSPACE   (-4)  /* reserved: workspace too small */
+#define SHPLB_E_WORKSPACE   (-4)  /* the problem needs more scratch than shplb_sparse_attn_prefill_static has */
 #define SHPLB_E_UNSUPPORTED (-5)  /* head_dim != 128, block not 64/128, too many sequences/blocks/heads */
 #define SHPLB_E_HIP         (-6)  /* a HIP call or kernel launch failed */
 
@@ -152,6 +152,26 @@ SHPLB_API int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* 
                                   const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
                                   void* out, float* lse_out, void* sched_stats_out,
                                   void* workspace, void* stream);
+
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the attention step of
+ * shplb_sparse_attn_prefill with its scratch (ordering histograms, work-item queues, tickets)
+ * in a static device array of SHPLB_STATIC_SCRATCH_BYTES inside the library instead of a
+ * workspace argument.  Same kernels, same results, bit for bit.  It allocates and frees
+ * nothing.  The scratch needed is about 100 bytes per (sequence, head, query block) row: the
+ * array covers about 80 000 rows (a 128K-token layer of 32 heads has 32 768); a larger
+ * problem is refused with SHPLB_E_WORKSPACE before any device work.
+ * Every GPU the library is used on holds its own copy of the array until the process ends.
+ * All calls on one GPU share it: the kernels rewrite everything they read, so calls in
+ * sequence on one stream need no clearing in between, but two calls that overlap on one GPU
+ * (different streams, different threads) race and must not be made.  The first call on a
+ * device looks up the array's address (hipGetSymbolAddress): make it once outside any
+ * stream capture.
+ *   Arguments as for shplb_sparse_attn_prefill, without the workspace. */
+#define SHPLB_STATIC_SCRATCH_BYTES (8 << 20)
+SHPLB_API int32_t shplb_sparse_attn_prefill_static(const shplb_problem* p, const void* q, const void* k,
+                                         const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
+                                         void* out, float* lse_out, void* sched_stats_out, void* stream);
 
 /* The same attention step with long rows cut along their selected key blocks
  * (the partition of Section 3.3 applied below the row: a work item is a row or a

@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     shplb_select_topk_per_head,
     shplb_sparse_attn_prefill,
     shplb_sparse_attn_prefill_split,
+    shplb_sparse_attn_prefill_static,
     shplb_split_workspace_bytes,
     shplb_strerror,
     shplb_workspace_bytes,

@@ -13,7 +13,7 @@ _LIB = None
 EXPORTS = [
     "shplb_num_rows", "shplb_max_blocks", "shplb_workspace_bytes", "shplb_score_layout", "shplb_sel_row_ptr",
     "shplb_sched_num_workgroups", "shplb_block_scores", "shplb_select_topk_per_head",
-    "shplb_sparse_attn_prefill", "shplb_split_workspace_bytes", "shplb_sparse_attn_prefill_split",
+    "shplb_sparse_attn_prefill", "shplb_sparse_attn_prefill_static", "shplb_split_workspace_bytes", "shplb_sparse_attn_prefill_split",
     "shplb_balance_heads", "shplb_shift_budgets", "shplb_block_mass",
     "shplb_recovery_curves", "shplb_probe_mfma_rate", "shplb_strerror",
 ]
@@ -83,6 +83,7 @@ def load_library():
     lib.shplb_block_scores.argtypes = [pp, vp, vp, vp, vp, vp]
     lib.shplb_select_topk_per_head.argtypes = [pp, vp, C.POINTER(i32), vp, vp, vp]
     lib.shplb_sparse_attn_prefill.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.shplb_sparse_attn_prefill_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.shplb_split_workspace_bytes.argtypes = [pp, i32, C.POINTER(i64)]
     lib.shplb_sparse_attn_prefill_split.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.shplb_balance_heads.argtypes = [C.POINTER(i64), i32, i32, i32, C.POINTER(i32), C.POINTER(i64)]
@@ -214,6 +215,14 @@ def shplb_sparse_attn_prefill(p: Problem, q, k, v, sel_ptr, sel_idx, out, lse_ou
                                                     _dev(sel_idx), _dev(out), _dev(lse_out),
                                                     _dev(sched_stats_out), _dev(workspace), _stream(stream)),
            "shplb_sparse_attn_prefill")
+
+
+def shplb_sparse_attn_prefill_static(p: Problem, q, k, v, sel_ptr, sel_idx, out, lse_out=None,
+                                     sched_stats_out=None, stream=None) -> None:
+    _check(load_library().shplb_sparse_attn_prefill_static(p.ref(), _dev(q), _dev(k), _dev(v), _dev(sel_ptr),
+                                                           _dev(sel_idx), _dev(out), _dev(lse_out),
+                                                           _dev(sched_stats_out), _stream(stream)),
+           "shplb_sparse_attn_prefill_static")
 
 
 def shplb_split_workspace_bytes(p: Problem, split_slots: int) -> int:

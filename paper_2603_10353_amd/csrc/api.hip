@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstring>
 #include <functional>
+#include <mutex>
 #include <numeric>
 #include <vector>
 
@@ -62,11 +63,11 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g) {
   return SHPLB_OK;
 }
 
-WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots) {
+WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots, bool with_pooled) {
   WorkspaceLayout w;
   int64_t off = 0;
-  w.qbar = off; off += align256(int64_t(g.meta.n_q_heads) * g.total_blocks * kHeadDim * 6);
-  w.kbar = off; off += align256(int64_t(g.meta.n_kv_heads) * g.total_blocks * kHeadDim * 6);
+  w.qbar = off; off += with_pooled ? align256(int64_t(g.meta.n_q_heads) * g.total_blocks * kHeadDim * 6) : 0;
+  w.kbar = off; off += with_pooled ? align256(int64_t(g.meta.n_kv_heads) * g.total_blocks * kHeadDim * 6) : 0;
   w.order_by_cost = off; off += align256(g.rows * 4);
   // Items: one per row plus the extra pieces of split rows.  split_length() keeps the pieces
   // within whatever number of slots it is given.
@@ -104,6 +105,34 @@ int32_t persistent_workgroups() {
 }  // namespace shplb
 
 using namespace shplb;
+
+// Scratch of the entry point that allocates nothing (shplb_sparse_attn_prefill_static): the
+// ordering kernels' histograms, the work-item queues and their tickets live here instead of in
+// a caller's workspace.  The array's name is only a host-side handle; its device address is
+// asked for once per device (every device holds its own copy) and that pointer is what the
+// kernels get.
+static __device__ __align__(256) unsigned char scratch[SHPLB_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[64] = {nullptr};
+
+// Device address of `scratch` on the current device.
+int32_t static_scratch(void** ptr_out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SHPLB_E_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return SHPLB_E_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *ptr_out = g_scratch_ptr[dev];
+  return SHPLB_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -201,17 +230,24 @@ namespace {
 
 int32_t attention_entry(const shplb_problem* p, const void* q, const void* k, const void* v,
                         const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse_out,
-                        void* sched_stats_out, void* workspace, int32_t split_slots, void* stream) {
-  if (!q || !k || !v || !sel_ptr || !sel_idx || !out || !workspace) return SHPLB_E_NULL;
+                        void* sched_stats_out, void* workspace, int32_t split_slots, void* stream,
+                        bool static_scratch_call = false) {
+  if (!q || !k || !v || !sel_ptr || !sel_idx || !out) return SHPLB_E_NULL;
   Geometry g;
   if (int32_t st = make_geometry(p, &g)) return st;
+  if (static_scratch_call) {
+    // the attention step's part of the workspace only (no pooled planes), inside the static array
+    if (make_layout(g, 0, false).total > SHPLB_STATIC_SCRATCH_BYTES) return SHPLB_E_WORKSPACE;
+    if (int32_t st = static_scratch(&workspace)) return st;
+  }
+  if (!workspace) return SHPLB_E_NULL;
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
        reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(out)) & 15)
     return SHPLB_E_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return SHPLB_E_SHAPE;
   const int32_t n_wg = persistent_workgroups();
   if (n_wg < 0) return n_wg;
-  const WorkspaceLayout w = make_layout(g, split_slots);
+  const WorkspaceLayout w = make_layout(g, split_slots, !static_scratch_call);
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (int32_t rc = launch_order(g, sel_ptr, w, ws, st)) return rc;
@@ -234,6 +270,12 @@ int32_t shplb_sparse_attn_prefill(const shplb_problem* p, const void* q, const v
                                   void* out, float* lse_out, void* sched_stats_out,
                                   void* workspace, void* stream) {
   return attention_entry(p, q, k, v, sel_ptr, sel_idx, out, lse_out, sched_stats_out, workspace, 0, stream);
+}
+
+int32_t shplb_sparse_attn_prefill_static(const shplb_problem* p, const void* q, const void* k,
+                                         const void* v, const int64_t* sel_ptr, const int32_t* sel_idx,
+                                         void* out, float* lse_out, void* sched_stats_out, void* stream) {
+  return attention_entry(p, q, k, v, sel_ptr, sel_idx, out, lse_out, sched_stats_out, nullptr, 0, stream, true);
 }
 
 int32_t shplb_split_workspace_bytes(const shplb_problem* p, int32_t split_slots, int64_t* bytes_out) {
@@ -377,7 +419,7 @@ const char* shplb_strerror(int32_t status) {
     case SHPLB_E_NULL: return "required pointer is null";
     case SHPLB_E_SHAPE: return "bad shape, stride, alignment, scale or cu_seqlens";
     case SHPLB_E_BUDGET: return "negative budget or cost, or partition cannot hold the units";
-    case SHPLB_E_WORKSPACE: return "workspace too small";
+    case SHPLB_E_WORKSPACE: return "problem needs more scratch than the static array holds";
     case SHPLB_E_UNSUPPORTED: return "unsupported configuration (head_dim 128, block 64/128, <=64 sequences, <=4096 blocks each)";
     case SHPLB_E_HIP: return "HIP call or kernel launch failed";
     default: return "unknown status";

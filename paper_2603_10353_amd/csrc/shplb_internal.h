@@ -64,7 +64,8 @@ struct WorkspaceLayout {
 
 int32_t make_geometry(const shplb_problem* p, Geometry* g);
 // split_slots: partial-result slots for rows split along the keys (0: rows stay whole)
-WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots = 0);
+// with_pooled = false leaves out the pooled planes (the attention step alone does not use them)
+WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots = 0, bool with_pooled = true);
 int32_t persistent_workgroups();   // for the current device; <0 on HIP error
 
 // Kernel launchers (each returns a SHPLB status).
