@@ -175,21 +175,24 @@ SHPLB_API int32_t shplb_sparse_attn_prefill_static(const shplb_problem* p, const
 
 /* The same attention step with long rows cut along their selected key blocks
  * (the partition of Section 3.3 applied below the row: a work item is a row or a
- * piece of one).  Rows that select more than max(16, ceil(2 * total / split_slots))
- * blocks, total = all selected blocks of the call, are cut into near-equal pieces;
- * each piece is dealt to a workgroup like a row, leaves its unnormalised result,
- * reference exponent and denominator in one of `split_slots` slots of the workspace
- * (65 KB each), and a merge pass after the attention launch combines the pieces
- * of a row in piece order (the softmax of Eq. 1 over the union of their keys).
- * Results equal those of shplb_sparse_attn_prefill up to fp32 rounding of the
- * merge and are bit-identical from run to run.  Finer items end a launch more
- * evenly; the slots and the merge cost HBM traffic: measured, whole rows were
- * faster on every shape tried, so this is an option, not the default.
- *   split_slots: 2 .. 65536; block must be 128.
+ * piece of one).  A row is cut into near-equal pieces (at most 64) when it selects
+ * more blocks than L = max(2048 keys, ceil(total / (2 * workgroups)), ceil(2 *
+ * total / split_slots)), total = all selected blocks of the call: rows that are
+ * a large part of a workgroup's average share (mid-length prompts with dense-like
+ * heads, few heads), never pieces so short that their fixed cost shows, and never
+ * more pieces than slots.  At long contexts and in launches of short rows nothing
+ * exceeds L and the call equals shplb_sparse_attn_prefill.
+ * Each piece is dealt to a workgroup like a row and leaves its unnormalised
+ * result, reference exponent and denominator in one of `split_slots` slots of the
+ * workspace (65 KB each); the piece of a row that finishes last combines the
+ * row's pieces in piece order (the softmax of Eq. 1 over the union of their
+ * keys) inside the same launch.  Results equal those of shplb_sparse_attn_prefill
+ * up to fp32 rounding of the combination and are bit-identical from run to run.
+ *   split_slots: 2 .. 65536 (4 * workgroups = 2048 never limit L).
  *   workspace: device, shplb_split_workspace_bytes(p, split_slots) bytes.
  *   Other arguments as for shplb_sparse_attn_prefill; sched_stats_out counts
  *   pieces as items.
- * Errors: SHPLB_E_UNSUPPORTED for split_slots out of range or block != 128. */
+ * Errors: SHPLB_E_UNSUPPORTED for split_slots out of range. */
 SHPLB_API int32_t shplb_split_workspace_bytes(const shplb_problem* p, int32_t split_slots,
                                     int64_t* bytes_out /*host*/);
 SHPLB_API int32_t shplb_sparse_attn_prefill_split(const shplb_problem* p, const void* q, const void* k,

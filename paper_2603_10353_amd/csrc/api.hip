@@ -71,10 +71,10 @@ WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots, bool with_po
   w.order_by_cost = off; off += align256(g.rows * 4);
   // Items: one per row plus the extra pieces of split rows.  split_length() keeps the pieces
   // within whatever number of slots it is given.
-  w.slot_capacity = g.meta.block == kSplitBlock ? std::max<int32_t>(split_slots, 0) : 0;
+  w.slot_capacity = std::max<int32_t>(split_slots, 0);
   w.item_capacity = g.rows + w.slot_capacity;
   w.items = off; off += align256(w.item_capacity * int64_t(sizeof(ItemRec)));
-  w.split_rows = off; off += align256((w.slot_capacity / 2 + 1) * int64_t(sizeof(SplitRow)));
+  w.split_done = off; off += align256((w.slot_capacity / 2 + 1) * int64_t(sizeof(uint32_t)));
   w.split_count = off; off += 256;
   w.part_o = off; off += align256(w.slot_capacity * kSlotFloatsO * 4);
   w.part_ml = off; off += align256(w.slot_capacity * kSlotFloatsML * 4);
@@ -250,17 +250,15 @@ int32_t attention_entry(const shplb_problem* p, const void* q, const void* k, co
   const WorkspaceLayout w = make_layout(g, split_slots, !static_scratch_call);
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (int32_t rc = launch_order(g, sel_ptr, w, ws, st)) return rc;
+  if (int32_t rc = launch_order(g, sel_ptr, w, ws, n_wg, st)) return rc;
   const WorkQueues wq{reinterpret_cast<const ItemRec*>(ws + w.items),
                       reinterpret_cast<const int32_t*>(ws + w.queue_begin),
                       reinterpret_cast<uint32_t*>(ws + w.tickets)};
   const SplitBuffers sb{reinterpret_cast<float*>(ws + w.part_o), reinterpret_cast<float*>(ws + w.part_ml),
-                        reinterpret_cast<const SplitRow*>(ws + w.split_rows),
-                        reinterpret_cast<const SplitCounters*>(ws + w.split_count), int32_t(w.slot_capacity)};
-  if (int32_t rc = launch_attention(g, q, k, v, sel_ptr, sel_idx, out, lse_out,
-                                    static_cast<shplb_wg_stats*>(sched_stats_out), wq, sb, n_wg, st))
-    return rc;
-  return w.slot_capacity > 0 ? launch_merge(g, sb, out, lse_out, st) : SHPLB_OK;
+                        reinterpret_cast<uint32_t*>(ws + w.split_done),
+                        reinterpret_cast<SplitCounters*>(ws + w.split_count), int32_t(w.slot_capacity)};
+  return launch_attention(g, q, k, v, sel_ptr, sel_idx, out, lse_out, static_cast<shplb_wg_stats*>(sched_stats_out),
+                          wq, sb, n_wg, st);
 }
 
 }  // namespace
@@ -282,7 +280,7 @@ int32_t shplb_split_workspace_bytes(const shplb_problem* p, int32_t split_slots,
   if (!bytes_out) return SHPLB_E_NULL;
   Geometry g;
   if (int32_t st = make_geometry(p, &g)) return st;
-  if (split_slots < 2 || split_slots > kSplitSlotsMax || g.meta.block != kSplitBlock) return SHPLB_E_UNSUPPORTED;
+  if (split_slots < 2 || split_slots > kSplitSlotsMax) return SHPLB_E_UNSUPPORTED;
   *bytes_out = make_layout(g, split_slots).total;
   return SHPLB_OK;
 }
@@ -292,7 +290,7 @@ int32_t shplb_sparse_attn_prefill_split(const shplb_problem* p, const void* q, c
                                         void* out, float* lse_out, void* sched_stats_out,
                                         void* workspace, int32_t split_slots, void* stream) {
   if (!p) return SHPLB_E_NULL;
-  if (split_slots < 2 || split_slots > kSplitSlotsMax || p->block != kSplitBlock) return SHPLB_E_UNSUPPORTED;
+  if (split_slots < 2 || split_slots > kSplitSlotsMax) return SHPLB_E_UNSUPPORTED;
   return attention_entry(p, q, k, v, sel_ptr, sel_idx, out, lse_out, sched_stats_out, workspace, split_slots,
                          stream);
 }

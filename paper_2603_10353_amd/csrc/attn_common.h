@@ -85,6 +85,140 @@ __device__ __forceinline__ float pair_sum(float x) {
   return a + b;
 }
 
+// Partial results of the pieces of split rows travel between workgroups of one launch, possibly
+// on different dies, whose L2 caches are not coherent with each other.  They are therefore written
+// and read with device-scope accesses (relaxed atomics of 8 bytes: stores that write through to the
+// level all dies see, loads that do not trust a die-local copy) instead of plain accesses between
+// device-wide fences: such a fence writes back and invalidates the whole L2 of the die, which costs
+// every other workgroup there its cached K/V tiles (measured: launches of a few hundred pieces took
+// three times as long).
+__device__ __forceinline__ void slot_store(float* p, float a, float b) {
+  const uint64_t w = uint64_t(__float_as_uint(a)) | uint64_t(__float_as_uint(b)) << 32;
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void slot_load(const float* p, float& a, float& b) {
+  const uint64_t w = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  a = __uint_as_float(uint32_t(w));
+  b = __uint_as_float(uint32_t(w >> 32));
+}
+// 16-byte device-scope load.  Issued as assembly (there is no 16-byte atomic load to ask the compiler
+// for); the data is not valid before slot_wait() has been called on it.
+__device__ __forceinline__ f32x4 slot_load16_issue(const float* p) {
+  f32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+// Wait for all outstanding loads; the values pass through so that no use can be scheduled above the wait.
+__device__ __forceinline__ void slot_wait(f32x4& a, f32x4& b, f32x4& c, f32x4& d) {
+  asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : : "memory");
+}
+__device__ __forceinline__ void slot_store1(float* p, float a) {
+  __hip_atomic_store(reinterpret_cast<uint32_t*>(p), __float_as_uint(a), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float slot_load1(const float* p) {
+  return __uint_as_float(__hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// Called by every thread of a workgroup whose item was a piece of a split row, after the piece's
+// partial result went to its slot (slot_store): the unnormalised output O_c, the sum l_c of its
+// probabilities, both relative to a reference exponent m_c (p = 2^(s*scale*log2e - m_c)).  The piece
+// is counted; the piece of a row that is counted last combines all of them.  Softmax over the union
+// of the pieces (Eq. 1 over the selected keys) is, with m = max_c m_c and w_c = 2^(m_c - m),
+//
+//     out = sum_c w_c O_c / sum_c w_c l_c,      lse = (m + log2 sum_c w_c l_c) ln 2,
+//
+// summed in piece order from the slots (the last piece reads its own result back like the
+// others), so the result depends neither on which piece finished last nor on slot numbers.
+// Order: every thread waits until its slot stores are done, the workgroup meets at a barrier, one
+// thread counts the piece with a device-scope atomic; whoever sees the count complete reads the slots
+// (and returns true).
+// The combination runs in two passes so that few dependent memory round trips remain: first one
+// thread per query turns the pieces' (m_c, l_c) into weights w_c / sum w_c l_c in LDS, then every
+// thread accumulates its 16 output chunks piece by piece, the 32 loads of a piece in flight together.
+//   out_row: output of the row's first query (head applied); lse_row: likewise, or null;
+//   n_valid: valid queries of the row (ragged last block); s_flag: one int of LDS;
+//   lds_w, lds_l: kMaxPieces * BQ floats of LDS each that nobody else uses until the workgroup's next barrier.
+constexpr int kMaxPieces = kSplitMaxPieces;
+template <int BQ, int THREADS>
+__device__ __attribute__((noinline)) bool finish_piece(const SplitBuffers& sb, int pieces, int first_slot, int split_index,
+                                                       uint16_t* out_row, int64_t q_stride_t, float* lse_row,
+                                                       int n_valid, int32_t* s_flag, float* lds_w, float* lds_l) {
+  // item records come from the ordering kernels; a malformed one must not index out of bounds
+  if (pieces < 2 || pieces > kMaxPieces || first_slot < 0 || first_slot + pieces > sb.slot_capacity ||
+      split_index < 0 || split_index > sb.slot_capacity / 2)
+    return false;
+  wait_vmem_all();
+  __syncthreads();
+  if (threadIdx.x == 0)
+    *s_flag = int(__hip_atomic_fetch_add(sb.done + split_index, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  __syncthreads();
+  if (*s_flag != pieces - 1) return false;
+  const float* part_o = sb.part_o + int64_t(first_slot) * kSlotFloatsO;
+  const float* part_ml = sb.part_ml + int64_t(first_slot) * kSlotFloatsML;
+  // pass 1: thread q < BQ: weights of the pieces for query q, already divided by the denominator
+  if (threadIdx.x < BQ) {
+    const int q_in = threadIdx.x;
+#pragma unroll 4
+    for (int c = 0; c < pieces; ++c) {              // independent loads, several in flight
+      lds_w[c * BQ + q_in] = slot_load1(part_ml + c * kSlotFloatsML + q_in);
+      lds_l[c * BQ + q_in] = slot_load1(part_ml + c * kSlotFloatsML + 128 + q_in);
+    }
+    float m = -INFINITY;
+    for (int c = 0; c < pieces; ++c) m = fmaxf(m, lds_w[c * BQ + q_in]);
+    float l = 0.0f;
+    for (int c = 0; c < pieces; ++c) {
+      const float m_c = lds_w[c * BQ + q_in];
+      const float w = m_c == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(m_c - m);
+      lds_w[c * BQ + q_in] = w;
+      l += w * lds_l[c * BQ + q_in];
+    }
+    const float inv = 1.0f / l;
+    for (int c = 0; c < pieces; ++c) lds_w[c * BQ + q_in] *= inv;
+    if (lse_row != nullptr && q_in < n_valid) lse_row[q_in] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+  }
+  __syncthreads();
+  // pass 2: the slots hold O in the order the attention kernels keep it in registers (slot_chunk()):
+  // chunk e = ((wave * 4 + dt) * 4 + rq) * 64 + lane is dims 32 dt + 8 rq + 4 (lane / 32) .. +3 of query
+  // 32 wave + lane % 32.  A thread owns chunks threadIdx.x + THREADS * u; a wave reads 1 KB runs.
+  constexpr int kChunks = BQ * (kHeadDim / 4) / THREADS;
+  f32x4 acc[kChunks];
+#pragma unroll
+  for (int u = 0; u < kChunks; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  static_assert(kChunks % 4 == 0, "chunks are awaited four at a time");
+  for (int c = 0; c < pieces; ++c) {
+    f32x4 o[kChunks];
+#pragma unroll
+    for (int u = 0; u < kChunks; ++u)
+      o[u] = slot_load16_issue(part_o + c * kSlotFloatsO + 4 * (threadIdx.x + THREADS * u));
+#pragma unroll
+    for (int u = 0; u < kChunks; u += 4) slot_wait(o[u], o[u + 1], o[u + 2], o[u + 3]);
+#pragma unroll
+    for (int u = 0; u < kChunks; ++u) {
+      const int e = threadIdx.x + THREADS * u;
+      const float w = lds_w[c * BQ + 32 * (e >> 10) + (e & 31)];
+      acc[u] += w * o[u];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kChunks; ++u) {
+    const int e = threadIdx.x + THREADS * u;
+    const int q_in = 32 * (e >> 10) + (e & 31);
+    const int d = 32 * ((e >> 8) & 3) + 8 * ((e >> 6) & 3) + 4 * ((e >> 5) & 1);
+    if (q_in >= n_valid) continue;                  // padding of a ragged last block
+    u32x2 w2;
+    w2.x = pack_bf16(acc[u].x, acc[u].y);
+    w2.y = pack_bf16(acc[u].z, acc[u].w);
+    *reinterpret_cast<u32x2*>(out_row + int64_t(q_in) * q_stride_t + d) = w2;
+  }
+  return true;
+}
+
+// Where lane `lane` of wave `wave` keeps its four accumulator values rq of dim tile dt in a slot: the
+// 64 lanes of a wave write one run of 1 KB (full cache lines, which write-through stores need).
+__device__ __forceinline__ int slot_chunk(int wave, int dt, int rq, int lane) {
+  return 4 * ((((wave * 4 + dt) * 4 + rq) << 6) + lane);
+}
+
 __device__ __forceinline__ uint32_t lds_offset_of(const void* p) {
   return uint32_t(size_t((__attribute__((address_space(3))) const char*)(p)));
 }

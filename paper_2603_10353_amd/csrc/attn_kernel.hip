@@ -36,7 +36,7 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                  const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
                  uint16_t* __restrict__ out, float* __restrict__ lse, shplb_wg_stats* __restrict__ stats,
-                 WorkQueues wq, int64_t total_tokens, float scale_log2) {
+                 WorkQueues wq, SplitBuffers sb, int64_t total_tokens, float scale_log2) {
   constexpr int kWaves = BQ / 32;
   constexpr int SUB = BQ / kKeysPerTile;            // 64-key sub-tiles per key block
   constexpr int kRoundRows = 4 * kWaves;            // rows one round of copies moves (4 per wave)
@@ -45,6 +45,7 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   __shared__ __attribute__((aligned(1024))) char k_lds[2][kTileBytes];
   __shared__ __attribute__((aligned(1024))) char v_lds[2][kTileBytes];
   __shared__ int32_t s_item;
+  __shared__ int32_t s_flag;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -82,14 +83,18 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     const int pos = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
     __syncthreads();
     if (pos < 0) break;
-    const int row = __builtin_amdgcn_readfirstlane(wq.items[pos].row);   // rows are never split at this block size
-    if (row < 0 || row >= meta.blk_begin[meta.n_seq] * meta.n_q_heads) continue;   // malformed item record
+    // the item: a row, or a piece of one (then it covers part of the row's selection and
+    // leaves a partial result in a slot instead of the output)
+    const ItemRec* item = wq.items + pos;
+    const int row = __builtin_amdgcn_readfirstlane(item->row);
+    const int n_sel = __builtin_amdgcn_readfirstlane(item->n_sel);
+    const int64_t sel_begin = item->sel_begin;
+    const int slot = __builtin_amdgcn_readfirstlane(item->slot);
+    if (row < 0 || row >= meta.blk_begin[meta.n_seq] * meta.n_q_heads || slot >= sb.slot_capacity) continue;
     int s, h, i, nb;
     decode_row(meta, row, s, h, i, nb);
     const int g = h / group;
     const int seq_begin = meta.tok_begin[s], seq_end = meta.tok_begin[s + 1];
-    const int64_t sel_begin = sel_ptr[row];
-    const int n_sel = int(sel_ptr[row + 1] - sel_begin);
     const int n_tiles = n_sel * SUB;
     if (n_sel <= 0) continue;          // malformed row: nothing to attend to
     if (my_items == 0) t_first = wall_clock64();
@@ -253,7 +258,24 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     // ---- normalise and store: lane holds, for its query, dims 32dt + 8(r/4) + 4hi + (r%4)
     {
       const float l_tot = l_run + __shfl_xor(l_run, 32);
-      if (q_tok < seq_end) {
+      if (slot >= 0) {
+        // a piece of a split row: O and l as they stand (relative to 2^m_ref), for finish_piece()
+        const int q_in = wave * 32 + n;
+        float* part = sb.part_o + int64_t(slot) * kSlotFloatsO;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            float* dst = part + slot_chunk(wave, dt, rq, lane);
+            slot_store(dst, acc_o[dt][4 * rq], acc_o[dt][4 * rq + 1]);
+            slot_store(dst + 2, acc_o[dt][4 * rq + 2], acc_o[dt][4 * rq + 3]);
+          }
+        if (hi == 0) {
+          float* ml = sb.part_ml + int64_t(slot) * kSlotFloatsML;
+          slot_store1(ml + q_in, m_ref);
+          slot_store1(ml + 128 + q_in, l_tot);
+        }
+      } else if (q_tok < seq_end) {
         const float inv = 1.0f / l_tot;
         uint16_t* dst = out + int64_t(q_tok) * st.q_t + int64_t(h) * st.q_h + 4 * hi;
 #pragma unroll
@@ -268,6 +290,14 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
         if (lse != nullptr && hi == 0)
           lse[int64_t(h) * total_tokens + q_tok] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
       }
+    }
+    if (slot >= 0) {
+      const int q0 = seq_begin + i * BQ;
+      finish_piece<BQ, 2 * BQ>(sb, item->pieces, item->first_slot, item->split_index,
+                               out + int64_t(q0) * st.q_t + int64_t(h) * st.q_h, st.q_t,
+                               lse != nullptr ? lse + int64_t(h) * total_tokens + q0 : nullptr,
+                               min(BQ, seq_end - q0), &s_flag, reinterpret_cast<float*>(&k_lds[0][0]),
+                                 reinterpret_cast<float*>(&v_lds[0][0]));
     }
     t_last = wall_clock64();
   }
@@ -287,12 +317,12 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 template <int BQ>
 void launch_one(const Geometry& g, const void* q, const void* k, const void* v, const int64_t* sel_ptr,
                 const int32_t* sel_idx, void* out, float* lse, shplb_wg_stats* stats,
-                WorkQueues wq, int32_t n_wg, hipStream_t stream) {
+                WorkQueues wq, SplitBuffers sb, int32_t n_wg, hipStream_t stream) {
   const float scale_log2 = g.scale * 1.4426950408889634f;
   hipLaunchKernelGGL((attn_kernel<BQ>), dim3(n_wg), dim3(2 * BQ), 0, stream, g.meta, g.st,
                      static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                      static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
-                     stats, wq, g.total_tokens, scale_log2);
+                     stats, wq, sb, g.total_tokens, scale_log2);
 }
 
 }  // namespace
@@ -303,7 +333,7 @@ int32_t launch_attention(const Geometry& g, const void* q, const void* k, const 
   if (g.meta.block == 128)
     launch_attention_pipe128(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, wq, sb, n_wg, stream);
   else
-    launch_one<64>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, wq, n_wg, stream);
+    launch_one<64>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, wq, sb, n_wg, stream);
   if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
   return SHPLB_OK;
 }

@@ -51,6 +51,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   __shared__ __attribute__((aligned(1024))) char k_lds[2][kTileBytes];
   __shared__ __attribute__((aligned(1024))) char v_lds[2][kTileBytes];
   __shared__ int32_t s_item;
+  __shared__ int32_t s_flag;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -388,21 +389,21 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     for (int nt = 0; nt < NT; ++nt) {
       const float l_tot = pair_sum(l_run[nt]);
       if (slot >= 0) {
-        // a piece of a split row: O and l as they stand (relative to 2^m_ref), for merge_kernel
+        // a piece of a split row: O and l as they stand (relative to 2^m_ref), for finish_piece()
         const int q_in = wave * QW + 32 * nt + n;
-        float* dst = sb.part_o + int64_t(slot) * kSlotFloatsO + q_in * kHeadDim + 4 * hi;
+        float* part = sb.part_o + int64_t(slot) * kSlotFloatsO;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
-            const f32x4 w = {acc_o[dt][nt][4 * rq], acc_o[dt][nt][4 * rq + 1], acc_o[dt][nt][4 * rq + 2],
-                             acc_o[dt][nt][4 * rq + 3]};
-            *reinterpret_cast<f32x4*>(dst + 32 * dt + 8 * rq) = w;
+            float* dst = part + slot_chunk(wave * NT + nt, dt, rq, lane);
+            slot_store(dst, acc_o[dt][nt][4 * rq], acc_o[dt][nt][4 * rq + 1]);
+            slot_store(dst + 2, acc_o[dt][nt][4 * rq + 2], acc_o[dt][nt][4 * rq + 3]);
           }
         if (hi == 0) {
           float* ml = sb.part_ml + int64_t(slot) * kSlotFloatsML;
-          ml[q_in] = m_ref[nt];
-          ml[128 + q_in] = l_tot;
+          slot_store1(ml + q_in, m_ref[nt]);
+          slot_store1(ml + 128 + q_in, l_tot);
         }
       } else if (q_tok[nt] < seq_end) {
         const float inv = 1.0f / l_tot;
@@ -420,6 +421,15 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
           lse[int64_t(h) * total_tokens + q_tok[nt]] =
               (m_ref[nt] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
       }
+    }
+    if (slot >= 0) {
+      // a piece: count it; the row's last piece to finish combines all of them into the output
+      const int q0 = seq_begin + i * BQ;
+      finish_piece<BQ, 256 / NT>(sb, item->pieces, item->first_slot, item->split_index,
+                                 out + int64_t(q0) * st.q_t + int64_t(h) * st.q_h, st.q_t,
+                                 lse != nullptr ? lse + int64_t(h) * total_tokens + q0 : nullptr,
+                                 min(BQ, seq_end - q0), &s_flag, reinterpret_cast<float*>(&k_lds[0][0]),
+                                 reinterpret_cast<float*>(&v_lds[0][0]));
     }
     t_last = wall_clock64();
   }

@@ -18,11 +18,11 @@
 //
 // When the caller provides slots for partial results (shplb_sparse_attn_prefill_split), rows
 // longer than split_length() are cut along their selected key blocks into near-equal pieces,
-// each an item of its own (sort 2 counts and places pieces instead of rows; the pieces of a
-// row sit next to each other, where the row would).  A piece leaves a partial result in a
-// slot of the workspace and merge_kernel combines the pieces of a row.  Slots and the list of
-// split rows are handed out through atomic counters, so their numbering varies between runs;
-// what is computed does not depend on it.
+// each an item of its own (the pieces of a row sit next to each other, where the row would).
+// A piece leaves a partial result in a slot of the workspace; the piece of a row that finishes
+// last combines them (finish_piece() in attn_common.h).  Slots and counter entries are handed
+// out through atomic counters, so their numbering varies between runs; what is computed does
+// not depend on it.
 #include "shplb_internal.h"
 
 namespace shplb {
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(1024) void order_scan_kernel(
 __global__ __launch_bounds__(kOrderChunk) void order_scatter_kernel(
     SeqMeta meta, const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ hist,
     const int32_t* __restrict__ bin_start, int32_t* __restrict__ order_by_cost,
-    int32_t* __restrict__ xcd_hist, int rows, int n_bins, int slot_capacity) {
+    int32_t* __restrict__ xcd_hist, int rows, int n_bins, int slot_capacity, int n_wg) {
   __shared__ int32_t bins[kOrderChunk];
   const int row = blockIdx.x * kOrderChunk + threadIdx.x;
   const int bin = row < rows ? min(cost_bin(sel_ptr, row), n_bins - 1) : -1;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kOrderChunk) void order_scatter_kernel(
   for (int x = 0; x < int(threadIdx.x); ++x) rank += bins[x] == bin;
   const int pos = bin_start[bin] + hist[int64_t(blockIdx.x) * n_bins + bin] + rank;
   order_by_cost[pos] = row;
-  const int64_t split_len = split_length(sel_ptr[rows] - sel_ptr[0], slot_capacity);
+  const int64_t split_len = split_length(sel_ptr[rows] - sel_ptr[0], slot_capacity, n_wg, meta.block);
   const int pieces = pieces_of(sel_ptr[row + 1] - sel_ptr[row], split_len);
   atomicAdd(&xcd_hist[(pos / kOrderChunk) * kXcds + xcd_of_row(meta, row)], pieces);
 }
@@ -153,20 +153,47 @@ __global__ __launch_bounds__(64 * kXcds) void queue_scan_kernel(
   }
 }
 
+// The items of one row: the row itself, or its pieces (then with a run of slots and a counter
+// of finished pieces).  Returns without writing if the slots or counters are exhausted, which
+// split_length() rules out.
+__device__ __forceinline__ void write_items(ItemRec* __restrict__ dst, int row, int64_t sel_begin, int64_t n_sel,
+                                            int pieces, uint32_t* __restrict__ split_done,
+                                            SplitCounters* __restrict__ split_count, int slot_capacity) {
+  int slot = -1, entry = -1;
+  if (pieces > 1) {
+    slot = int(atomicAdd(&split_count->n_slots, uint32_t(pieces)));
+    if (slot + pieces > slot_capacity) return;
+    entry = int(atomicAdd(&split_count->n_rows, 1u));
+    if (entry >= slot_capacity / 2 + 1) return;
+    split_done[entry] = 0;
+  }
+  for (int c = 0; c < pieces; ++c) {
+    const int64_t first = piece_begin(n_sel, pieces, c);
+    ItemRec rec;
+    rec.row = row;
+    rec.n_sel = int32_t(max(piece_begin(n_sel, pieces, c + 1) - first, int64_t(0)));
+    rec.sel_begin = sel_begin + first;
+    rec.slot = pieces > 1 ? slot + c : -1;
+    rec.pieces = pieces;
+    rec.first_slot = slot;
+    rec.split_index = entry;
+    dst[c] = rec;
+  }
+}
+
 // Sort 2, pass 3: write the items of the cost-sorted rows into their die's queue.  A row's
-// place is the number of pieces of earlier rows of the same die; a split row takes a run of
-// slots and an entry in the list the merge works through.
+// place is the number of pieces of earlier rows of the same die.
 __global__ __launch_bounds__(kOrderChunk) void queue_scatter_kernel(
     SeqMeta meta, const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ order_by_cost,
     const int32_t* __restrict__ xcd_hist, const int32_t* __restrict__ queue_begin, ItemRec* __restrict__ items,
-    SplitRow* __restrict__ split_rows, SplitCounters* __restrict__ split_count, int rows, int item_capacity,
-    int slot_capacity) {
+    uint32_t* __restrict__ split_done, SplitCounters* __restrict__ split_count, int rows, int item_capacity,
+    int slot_capacity, int n_wg) {
   __shared__ int32_t die[kOrderChunk];
   __shared__ int32_t n_pieces[kOrderChunk];
   const int pos = blockIdx.x * kOrderChunk + threadIdx.x;
   const int row = pos < rows ? order_by_cost[pos] : -1;
   const int x = row >= 0 ? xcd_of_row(meta, row) : -1;
-  const int64_t split_len = split_length(sel_ptr[rows] - sel_ptr[0], slot_capacity);
+  const int64_t split_len = split_length(sel_ptr[rows] - sel_ptr[0], slot_capacity, n_wg, meta.block);
   const int64_t sel_begin = row >= 0 ? sel_ptr[row] : 0;
   const int64_t n_sel = row >= 0 ? sel_ptr[row + 1] - sel_begin : 0;
   const int pieces = pieces_of(n_sel, split_len);
@@ -178,50 +205,41 @@ __global__ __launch_bounds__(kOrderChunk) void queue_scatter_kernel(
   for (int t = 0; t < int(threadIdx.x); ++t) before += die[t] == x ? n_pieces[t] : 0;
   const int dst = queue_begin[x] + xcd_hist[blockIdx.x * kXcds + x] + before;
   if (dst < 0 || dst + pieces > item_capacity) return;   // never taken (see split_length); keeps stores in bounds
-  int slot = -1;
-  if (pieces > 1) {
-    slot = int(atomicAdd(&split_count->n_slots, uint32_t(pieces)));
-    if (slot + pieces > slot_capacity) return;           // never taken either
-    const uint32_t e = atomicAdd(&split_count->n_rows, 1u);
-    if (e >= uint32_t(slot_capacity / 2 + 1)) return;
-    split_rows[e] = SplitRow{row, slot, pieces, 0};
-  }
-  for (int c = 0; c < pieces; ++c) {
-    const int64_t first = piece_begin(n_sel, pieces, c);
-    ItemRec rec;
-    rec.row = row;
-    rec.n_sel = int32_t(max(piece_begin(n_sel, pieces, c + 1) - first, int64_t(0)));
-    rec.sel_begin = sel_begin + first;
-    rec.slot = pieces > 1 ? slot + c : -1;
-    rec.reserved[0] = rec.reserved[1] = rec.reserved[2] = 0;
-    items[dst + c] = rec;
-  }
+  write_items(items + dst, row, sel_begin, n_sel, pieces, split_done, split_count, slot_capacity);
 }
 
 // Both sorts in one workgroup, for launches of few rows (prompts of a few thousand tokens, a
 // part's share of a layer), where five dependent launches would cost more than the sorting.
 // One counting sort over the combined key (die, descending cost) with the histogram in LDS:
-// count, scan, place.  Rows of equal key are placed in the order their atomics arrive, so
-// unlike the two-sort path the order among equal costs is not fixed; it decides only which
-// workgroup takes which of two equally long rows.
+// count, scan, place; a row counts as many items as it has pieces.  Rows of equal key are
+// placed in the order their atomics arrive, so unlike the two-sort path the order among equal
+// costs is not fixed; it decides only which workgroup takes which of two equally long rows.
 constexpr int kSmallThreads = 1024;
 constexpr int kSmallKeys = 16384;     // LDS histogram entries: kXcds * (cost bins) must fit
 constexpr int kSmallRows = 16384;
 
 __global__ __launch_bounds__(kSmallThreads) void order_small_kernel(
     SeqMeta meta, const int64_t* __restrict__ sel_ptr, ItemRec* __restrict__ items,
-    int32_t* __restrict__ queue_begin, uint32_t* __restrict__ tickets, int rows, int n_bins) {
+    int32_t* __restrict__ queue_begin, uint32_t* __restrict__ tickets, uint32_t* __restrict__ split_done,
+    SplitCounters* __restrict__ split_count, int rows, int n_bins, int item_capacity, int slot_capacity,
+    int n_wg) {
   __shared__ int32_t slot[kSmallKeys];               // count per key, then next free position per key
   __shared__ int32_t wave_sum[kSmallThreads / 64];
   const int tid = threadIdx.x;
   const int n_keys = kXcds * n_bins;
   for (int x = tid; x < n_keys; x += kSmallThreads) slot[x] = 0;
   if (tid < kXcds) tickets[tid * kTicketStride] = 0;
-  __syncthreads();
+  if (tid == 0) {
+    split_count->n_slots = 0;
+    split_count->n_rows = 0;
+  }
+  __syncthreads();                                   // also orders the counters' reset before their use below
+  const int64_t split_len = split_length(sel_ptr[rows] - sel_ptr[0], slot_capacity, n_wg, meta.block);
   auto key_of = [&](int row) {
     return xcd_of_row(meta, row) * n_bins + (n_bins - 1 - min(cost_bin(sel_ptr, row), n_bins - 1));
   };
-  for (int row = tid; row < rows; row += kSmallThreads) atomicAdd(&slot[key_of(row)], 1);
+  auto pieces_of_row = [&](int row) { return pieces_of(sel_ptr[row + 1] - sel_ptr[row], split_len); };
+  for (int row = tid; row < rows; row += kSmallThreads) atomicAdd(&slot[key_of(row)], pieces_of_row(row));
   __syncthreads();
   // exclusive scan over the keys: a thread owns a run of consecutive keys
   const int per = (n_keys + kSmallThreads - 1) / kSmallThreads;
@@ -244,23 +262,22 @@ __global__ __launch_bounds__(kSmallThreads) void order_small_kernel(
     if (x % n_bins == 0) queue_begin[x / n_bins] = run;   // first key of a die: its queue starts here
     run += c;
   }
-  if (tid == 0) queue_begin[kXcds] = rows;
+  if (tid == kSmallThreads - 1) queue_begin[kXcds] = run;    // the last thread's run ends at the item count
   __syncthreads();
   for (int row = tid; row < rows; row += kSmallThreads) {
-    ItemRec rec;                                     // rows stay whole on this path
-    rec.row = row;
-    rec.sel_begin = sel_ptr[row];
-    rec.n_sel = int32_t(max(sel_ptr[row + 1] - rec.sel_begin, int64_t(0)));
-    rec.slot = -1;
-    rec.reserved[0] = rec.reserved[1] = rec.reserved[2] = 0;
-    items[atomicAdd(&slot[key_of(row)], 1)] = rec;
+    const int64_t sel_begin = sel_ptr[row];
+    const int64_t n_sel = max(sel_ptr[row + 1] - sel_begin, int64_t(0));
+    const int pieces = pieces_of(n_sel, split_len);
+    const int dst = atomicAdd(&slot[key_of(row)], pieces);
+    if (dst < 0 || dst + pieces > item_capacity) continue;   // never taken (see split_length)
+    write_items(items + dst, row, sel_begin, n_sel, pieces, split_done, split_count, slot_capacity);
   }
 }
 
 }  // namespace
 
 int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceLayout& w,
-                     char* workspace, hipStream_t stream) {
+                     char* workspace, int32_t n_wg, hipStream_t stream) {
   const int rows = int(g.rows);
   const int n_chunks = (rows + kOrderChunk - 1) / kOrderChunk;
   const int n_bins = min(g.max_nb + 1, kCostBins);
@@ -268,14 +285,15 @@ int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceL
   int32_t* bin_start = reinterpret_cast<int32_t*>(workspace + w.bin_start);
   int32_t* order_by_cost = reinterpret_cast<int32_t*>(workspace + w.order_by_cost);
   ItemRec* items = reinterpret_cast<ItemRec*>(workspace + w.items);
-  SplitRow* split_rows = reinterpret_cast<SplitRow*>(workspace + w.split_rows);
+  uint32_t* split_done = reinterpret_cast<uint32_t*>(workspace + w.split_done);
   SplitCounters* split_count = reinterpret_cast<SplitCounters*>(workspace + w.split_count);
   int32_t* xcd_hist = reinterpret_cast<int32_t*>(workspace + w.xcd_hist);
   int32_t* queue_begin = reinterpret_cast<int32_t*>(workspace + w.queue_begin);
   uint32_t* tickets = reinterpret_cast<uint32_t*>(workspace + w.tickets);
-  if (w.slot_capacity == 0 && rows <= kSmallRows && kXcds * n_bins <= kSmallKeys) {
+  if (rows <= kSmallRows && kXcds * n_bins <= kSmallKeys) {
     hipLaunchKernelGGL(order_small_kernel, dim3(1), dim3(kSmallThreads), 0, stream, g.meta, sel_ptr, items,
-                       queue_begin, tickets, rows, n_bins);
+                       queue_begin, tickets, split_done, split_count, rows, n_bins, int(w.item_capacity),
+                       int(w.slot_capacity), n_wg);
     if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
     return SHPLB_OK;
   }
@@ -283,12 +301,12 @@ int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceL
                      rows, n_bins);
   hipLaunchKernelGGL(order_scan_kernel, dim3(1), dim3(1024), 0, stream, hist, bin_start, n_chunks, n_bins);
   hipLaunchKernelGGL(order_scatter_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, g.meta, sel_ptr, hist,
-                     bin_start, order_by_cost, xcd_hist, rows, n_bins, int(w.slot_capacity));
+                     bin_start, order_by_cost, xcd_hist, rows, n_bins, int(w.slot_capacity), n_wg);
   hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(64 * kXcds), 0, stream, xcd_hist, queue_begin, tickets,
                      split_count, n_chunks);
   hipLaunchKernelGGL(queue_scatter_kernel, dim3(n_chunks), dim3(kOrderChunk), 0, stream, g.meta, sel_ptr,
-                     order_by_cost, xcd_hist, queue_begin, items, split_rows, split_count, rows,
-                     int(w.item_capacity), int(w.slot_capacity));
+                     order_by_cost, xcd_hist, queue_begin, items, split_done, split_count, rows,
+                     int(w.item_capacity), int(w.slot_capacity), n_wg);
   if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
   return SHPLB_OK;
 }

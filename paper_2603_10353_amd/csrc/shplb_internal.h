@@ -13,9 +13,11 @@ constexpr int kOrderChunk = 256;      // rows per workgroup in the ordering kern
 constexpr int kXcds = 8;              // accelerator dies (XCDs) of an MI355X, each with its own L2
 constexpr int kTicketStride = 16;     // uint32 slots between two queue tickets (one 64-byte line each)
 constexpr int kSplitSlotsMax = 1 << 16;   // most partial-result slots a caller may ask for (64 KB + 1 KB each)
-constexpr int kSplitMinBlocks = 16;   // a piece of a split row is never shorter than about this many key blocks
-constexpr int kSplitBlock = 128;      // rows are split only at this block size (the pipelined kernel)
-constexpr int64_t kSlotFloatsO = 128 * kHeadDim;   // one partial result: unnormalised O of 128 queries ...
+constexpr int kSplitMinTiles = 32;    // a piece of a split row covers at least this many 64-key tiles: a piece costs
+                                      // about 7 us more than it computes for (write-through stores of its partial
+                                      // result, the count) and a merge 12-15 us; 32 tiles are about 50 us of work
+constexpr int kSplitShare = 2;        // rows longer than 1/kSplitShare of a workgroup's average share are split
+constexpr int64_t kSlotFloatsO = 128 * kHeadDim;   // one partial result: unnormalised O of up to 128 queries ...
 constexpr int64_t kSlotFloatsML = 2 * 128;         // ... and their reference exponent and denominator
 
 // Sequence geometry, passed to kernels by value (about 1 KB of kernel arguments).
@@ -49,7 +51,7 @@ struct WorkspaceLayout {
   int64_t qbar, kbar;        // pooled blocks as three bf16 planes, each [H][total_blocks][128]
   int64_t order_by_cost;     // int32 [rows]: rows by descending cost (intermediate)
   int64_t items;             // ItemRec [item_capacity]: the work items, one queue per XCD after the other
-  int64_t split_rows;        // SplitRow [slot_capacity / 2]: the rows that were split, in no particular order
+  int64_t split_done;        // uint32 [slot_capacity / 2 + 1]: pieces finished, per split row
   int64_t split_count;       // SplitCounters
   int64_t part_o;            // float [slot_capacity][128][kHeadDim]: partial results of the pieces
   int64_t part_ml;           // float [slot_capacity][2][128]
@@ -74,7 +76,7 @@ int32_t launch_pool_scores(const Geometry& g, const void* q, const void* k, floa
 int32_t launch_select(const Geometry& g, const float* scores, const int64_t* sel_ptr,
                       int32_t* sel_idx, hipStream_t stream);
 int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceLayout& w,
-                     char* workspace, hipStream_t stream);
+                     char* workspace, int32_t n_wg, hipStream_t stream);
 int32_t launch_mfma_rate(int random_operands, int iters, int n_workgroups, void* scratch, hipStream_t stream);
 int32_t launch_block_mass(const Geometry& g, const void* q, const void* k, float* mass, hipStream_t stream);
 // One work item of an attention launch: a row, or one piece of a row that was split along
@@ -84,31 +86,38 @@ struct alignas(32) ItemRec {
   int32_t n_sel;        // selected key blocks this item covers
   int64_t sel_begin;    // index of its first one in sel_idx
   int32_t slot;         // partial-result slot it writes, or -1: the item is the whole row and writes the output
-  int32_t reserved[3];
-};
-
-// A row that was split: its pieces wrote partial results to slots [slot, slot + pieces).
-struct SplitRow {
-  int32_t row, slot, pieces, reserved;
+  int32_t pieces;       // pieces of its row (1: whole row)
+  int32_t first_slot;   // slot of the row's first piece; the row's pieces hold slots first_slot .. + pieces - 1
+  int32_t split_index;  // the row's entry in the finished-pieces counters
 };
 
 struct SplitCounters {
   uint32_t n_slots, n_rows;   // slots handed out, rows split (zeroed by the ordering kernels)
 };
 
-// Longest item, in key blocks, for a launch whose rows select total_cost blocks in all and
-// whose workspace has room for slot_capacity partial results (0: never split).  Rows longer
-// than this are cut into near-equal pieces so that no single item is a large part of a
-// workgroup's share (total / workgroups) and the launch ends evenly.  The length also bounds
-// the slots in use: a split row of n blocks has ceil(n / len) < 2 n / len pieces, so all
-// split rows together have fewer than 2 total / len <= slot_capacity.
-__host__ __device__ inline int64_t split_length(int64_t total_cost, int slot_capacity) {
+// Longest item, in key blocks, of a launch whose rows select total_cost blocks in all, run by
+// n_wg persistent workgroups, with room for slot_capacity partial results (0: never split).
+// Rows longer than this are cut into near-equal pieces, so that no single item is a large
+// part of a workgroup's average share (total / n_wg) and a launch of few rows still fills the
+// chip.  Three lower bounds: a piece covers at least kSplitMinTiles key tiles (an item's fixed
+// cost must stay small beside its work); no longer than needed (1/kSplitShare of the share:
+// at long contexts nothing is split); and the pieces must fit the slots: a split row of n
+// blocks has ceil(n / len) < 2 n / len pieces, so all split rows together have fewer than
+// 2 total / len <= slot_capacity.
+__host__ __device__ inline int64_t split_length(int64_t total_cost, int slot_capacity, int n_wg, int block) {
   if (slot_capacity < 2) return int64_t(1) << 40;
-  const int64_t len = (2 * total_cost + slot_capacity - 1) / slot_capacity;
-  return len < kSplitMinBlocks ? kSplitMinBlocks : len;
+  int64_t len = kSplitMinTiles * 64 / block;
+  const int64_t fit = (2 * total_cost + slot_capacity - 1) / slot_capacity;
+  const int64_t share = (total_cost + int64_t(n_wg) * kSplitShare - 1) / (int64_t(n_wg) * kSplitShare);
+  if (fit > len) len = fit;
+  if (share > len) len = share;
+  return len;
 }
+constexpr int kSplitMaxPieces = 64;   // pieces of one row (their weights meet in a fixed piece of LDS)
 __host__ __device__ inline int pieces_of(int64_t n_sel, int64_t split_len) {
-  return n_sel > split_len ? int((n_sel + split_len - 1) / split_len) : 1;
+  if (n_sel <= split_len) return 1;
+  const int64_t p = (n_sel + split_len - 1) / split_len;
+  return int(p < kSplitMaxPieces ? p : kSplitMaxPieces);
 }
 // piece c of a row of n selected blocks cut into p pieces covers [piece_begin(c), piece_begin(c + 1))
 __host__ __device__ inline int64_t piece_begin(int64_t n_sel, int p, int c) { return n_sel * c / p; }
@@ -120,17 +129,14 @@ struct WorkQueues {
   uint32_t* tickets;           // [kXcds * kTicketStride], zeroed by the ordering kernels
 };
 
-// Where the pieces of split rows leave their results, and the list the merge runs over.
+// Where the pieces of split rows leave their results, and the per-row counts of finished pieces.
 struct SplitBuffers {
   float* part_o;
   float* part_ml;
-  const SplitRow* rows;
-  const SplitCounters* count;
+  uint32_t* done;              // [slot_capacity / 2 + 1], zeroed by the ordering kernels
+  SplitCounters* count;
   int32_t slot_capacity;
 };
-
-// Combine the partial results of split rows into out and lse (merge_kernel.hip).
-int32_t launch_merge(const Geometry& g, SplitBuffers sb, void* out, float* lse, hipStream_t stream);
 
 int32_t launch_attention(const Geometry& g, const void* q, const void* k, const void* v,
                          const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,

@@ -91,13 +91,9 @@ def test_long_and_short_rows_mixed():
     assert st["n_items"].sum() == run.rows
 
 
-@pytest.mark.parametrize("split_slots", [256, 1024])
-def test_long_rows_split_along_keys_and_merged(split_slots):
-    # shplb_sparse_attn_prefill_split on the same mixed case: with 1024 slots every row of more
-    # than 16 selected blocks is cut into pieces, with 256 slots only those of more than 22 are (the cut
-    # length rises so that the pieces fit the slots).  Compared with the oracle like the plain
-    # entry point, and with the plain entry point's own output.
-    wl = make_custom([128 * 40 + 37, 128 * 11], 4, 2, 128, [999, 999, 23, 3, 999, 18, 2, 7], seed=61, name="split")
+def _split_against_whole_rows(wl, split_slots, min_pieces_of_longest):
+    """shplb_sparse_attn_prefill_split against the oracle (like the plain entry point) and against
+    the plain entry point's own output; twice, for run-to-run identity."""
     run = _gpu()(wl).run_all()
     o_plain, l_plain = run.out.clone(), run.lse.clone()
     run.out.zero_(); run.lse.zero_()
@@ -108,10 +104,14 @@ def test_long_rows_split_along_keys_and_merged(split_slots):
     out_o, lse_o = orc.sparse_attention(wl.q, wl.k, wl.v, wl.cu_seqlens, wl.block, ptr_o, run.sel_idx_host(), None, None)
     wa, wr, wl_ = compare_output(run.out_host(), out_o, run.lse_host(), lse_o)
     st = run.stats_host()
-    print("  split_slots %d: items %d for %d rows, out max abs %.3g max rel %.3g" % (
-        split_slots, st["n_items"].sum(), run.rows, wa, wr), flush=True)
+    print("  %s split_slots %d: items %d for %d rows, out max abs %.3g max rel %.3g lse %.3g" % (
+        wl.name, split_slots, st["n_items"].sum(), run.rows, wa, wr, wl_), flush=True)
     assert st["cost_blocks"].sum() == run.sel_ptr_host[-1]      # every selected block visited exactly once
-    assert st["n_items"].sum() > run.rows                       # more items than rows: pieces
+    # more items than rows: pieces; the longest row alone accounts for its share of the extra ones
+    assert st["n_items"].sum() >= run.rows + min_pieces_of_longest - 1
+    if min_pieces_of_longest == 1:
+        assert st["n_items"].sum() == run.rows
+        assert torch.equal(run.out.view(torch.int16), o_plain.view(torch.int16)) and torch.equal(run.lse, l_plain)
     # against the unsplit result: the same sums in another order
     d = (run.out.float() - o_plain.float()).abs().max().item()
     assert d <= 2.0 ** -6, d
@@ -120,8 +120,39 @@ def test_long_rows_split_along_keys_and_merged(split_slots):
     run.out.zero_(); run.lse.zero_()
     run.attn_split_step(split_slots)
     torch.cuda.synchronize()
-    assert torch.equal(run.out.view(torch.int16), o1.view(torch.int16))   # slot numbering does not matter
+    assert torch.equal(run.out.view(torch.int16), o1.view(torch.int16))   # neither slot numbers nor who merges matter
     assert torch.equal(run.lse, l1)
+    return run
+
+
+@pytest.mark.parametrize("split_slots", [128, 1024])
+def test_long_rows_split_along_keys_and_merged(split_slots):
+    # The mixed case above through shplb_sparse_attn_prefill_split: 2741 selected blocks.  With 1024
+    # slots every row of more than 16 blocks is cut (the 41-block rows into 3 pieces), with 128 slots
+    # only rows of more than 43 would be: none, and the call must equal the plain one bit for bit.
+    # The piece of a row that finishes last merges.
+    wl = make_custom([128 * 40 + 37, 128 * 11], 4, 2, 128, [999, 999, 23, 3, 999, 18, 2, 7], seed=61, name="split")
+    _split_against_whole_rows(wl, split_slots, 3 if split_slots == 1024 else 1)
+
+
+def test_split_rows_block_64_many_pieces():
+    # 64-token blocks (the non-pipelined kernel): rows of up to 141 blocks are cut into up to five
+    # pieces of at least 32 blocks; GQA, ragged tail, a second sequence of one block
+    wl = make_custom([64 * 140 + 21, 50], 4, 2, 64, [999, 70, 2, 9, 999, 3, 5, 999], seed=62, name="split64")
+    _split_against_whole_rows(wl, 2048, 5)
+
+
+def test_split_leaves_short_rows_whole():
+    # configuration 0 (8 heads, 2K tokens, block 64): no row reaches the shortest piece length, so the
+    # split entry point must do exactly what the plain one does
+    wl = make_workload(0)
+    run = _gpu()(wl).run_all()
+    o_plain, l_plain = run.out.clone(), run.lse.clone()
+    run.out.zero_(); run.lse.zero_()
+    run.attn_split_step(1024)
+    torch.cuda.synchronize()
+    assert run.stats_host()["n_items"].sum() == run.rows
+    assert torch.equal(run.out.view(torch.int16), o_plain.view(torch.int16)) and torch.equal(run.lse, l_plain)
 
 
 @pytest.mark.parametrize("block", [64, 128])

@@ -82,7 +82,7 @@ def test_argument_validation():
     with pytest.raises(S.ShplbError) as e:
         S.shplb_select_topk_per_head(p, None, [2, 2, 2, 2], None, None)
     assert e.value.status == -1
-    # the split variant: slot count and block size are checked on the host, before anything else
+    # the split variant: the slot count is checked on the host, before anything else
     assert S.shplb_split_workspace_bytes(p, 64) > S.shplb_workspace_bytes(p) + 64 * 65536
     for bad in (0, 1, -5, 65537):
         with pytest.raises(S.ShplbError) as e:
@@ -92,9 +92,7 @@ def test_argument_validation():
             S.shplb_sparse_attn_prefill_split(p, None, None, None, None, None, None, split_slots=bad)
         assert e.value.status == -5
     p64 = S.Problem(**dict(ok, block=64))
-    with pytest.raises(S.ShplbError) as e:
-        S.shplb_split_workspace_bytes(p64, 64)
-    assert e.value.status == -5
+    assert S.shplb_split_workspace_bytes(p64, 64) > S.shplb_workspace_bytes(p64) + 64 * 65536
     with pytest.raises(S.ShplbError) as e:
         S.shplb_sparse_attn_prefill_split(p, None, None, None, None, None, None, split_slots=64)
     assert e.value.status == -1
