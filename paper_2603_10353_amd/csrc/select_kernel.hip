@@ -1,4 +1,6 @@
 // Per-head top-k key-block selection: one wavefront per (sequence, head, query block) row.
+#include <type_traits>
+
 #include "shplb_internal.h"
 
 namespace shplb {
@@ -13,51 +15,49 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 
 __device__ __forceinline__ int popc64(uint64_t m) { return __builtin_popcountll(m); }
 
-// SLOTS * 64 >= number of blocks of the longest sequence.
-//
+// Maximum over the 64 lanes, as a scalar.  Four data-parallel-primitive steps make every lane of a
+// row of 16 hold its row's maximum (exchange inside pairs, inside quads, mirror inside 8, mirror
+// inside 16), then one lane per row is read: no LDS round trips, unlike six shuffle steps.
+__device__ __forceinline__ uint32_t wave_max(uint32_t x) {
+  auto dpp = [](uint32_t v, auto ctrl) {
+    return uint32_t(__builtin_amdgcn_update_dpp(0, int(v), decltype(ctrl)::value, 0xf, 0xf, false));
+  };
+  x = max(x, dpp(x, std::integral_constant<int, 0xb1>{}));    // quad_perm [1,0,3,2]
+  x = max(x, dpp(x, std::integral_constant<int, 0x4e>{}));    // quad_perm [2,3,0,1]
+  x = max(x, dpp(x, std::integral_constant<int, 0x141>{}));   // row_half_mirror
+  x = max(x, dpp(x, std::integral_constant<int, 0x140>{}));   // row_mirror
+  const uint32_t a = __builtin_amdgcn_readlane(int(x), 0), b = __builtin_amdgcn_readlane(int(x), 16);
+  const uint32_t c = __builtin_amdgcn_readlane(int(x), 32), d = __builtin_amdgcn_readlane(int(x), 48);
+  return max(max(a, b), max(c, d));
+}
+
 // The row keeps block 0 and block i, then the `want` best of the candidates 1..i-1
 // under the total order (score descending, index ascending).  The wave finds the
 // want-th largest key t by a bitwise search (largest t with count(key >= t) >= want;
 // at most 32 steps, usually about a dozen), takes every key > t, and fills the
 // remainder with the lowest-index keys equal to t.  Output is written in ascending
 // block order.
+//
+// SLOTS * 64 > i: lane l holds the candidates l, 64 + l, ... in SLOTS registers.  The body is
+// instantiated for 2, 4, 8, ... slots and a row takes the smallest that holds it, so that
+// every loop over the slots is unrolled without a test per slot and short rows (the early
+// query blocks of every head) do not pay for long ones.
 template <int SLOTS>
-__global__ __launch_bounds__(256) void select_kernel(
-    SeqMeta meta, const float* __restrict__ scores, const int64_t* __restrict__ sel_ptr,
-    int32_t* __restrict__ sel_idx, int32_t rows) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  int s, h, i, nb;
-  decode_row(meta, row, s, h, i, nb);
-  const int64_t begin = sel_ptr[row];
-  int n = int(sel_ptr[row + 1] - begin);
-  n = min(n, i + 1);                            // never more than the causal-visible blocks
-  if (n <= 0) return;
-  int32_t* out = sel_idx + begin;
-  if (lane == 0) {
-    out[0] = 0;
-    if (n >= 2) out[n - 1] = i;
-  }
-  const int want = n - 2;                       // picks among candidates 1..i-1
-  const int n_cand = i - 1;
-  if (want <= 0) return;
-  const float* srow = scores + meta.score_off[s] + (int64_t(h) * nb + i) * nb;
-
+__device__ __forceinline__ void select_row(const float* __restrict__ srow, int32_t* __restrict__ out, int i,
+                                           int want, int lane) {
   uint32_t key[SLOTS];
-  const int slots = (i + 63) >> 6;              // slots that hold at least one candidate
 #pragma unroll
   for (int c = 0; c < SLOTS; ++c) {
     const int j = c * 64 + lane;
     key[c] = 0;                                 // 0 is below every real key (keys of finite floats are > 0)
-    if (c < slots && j >= 1 && j < i) key[c] = order_key(srow[j]);
+    if (j >= 1 && j < i) key[c] = order_key(srow[j]);
   }
 
-  if (want >= n_cand) {                         // budget covers every candidate
+  if (want >= i - 1) {                          // budget covers every candidate
 #pragma unroll
     for (int c = 0; c < SLOTS; ++c) {
       const int j = c * 64 + lane;
-      if (c < slots && j >= 1 && j < i) out[j] = j;
+      if (j >= 1 && j < i) out[j] = j;
     }
     return;
   }
@@ -69,15 +69,12 @@ __global__ __launch_bounds__(256) void select_kernel(
   uint32_t kmax = 0, kmin = 0xffffffffu;
 #pragma unroll
   for (int c = 0; c < SLOTS; ++c)
-    if (c < slots && key[c] != 0) {
+    if (key[c] != 0) {
       kmax = max(kmax, key[c]);
       kmin = min(kmin, key[c]);
     }
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) {
-    kmax = max(kmax, uint32_t(__shfl_xor(int(kmax), d)));
-    kmin = min(kmin, uint32_t(__shfl_xor(int(kmin), d)));
-  }
+  kmax = wave_max(kmax);
+  kmin = ~wave_max(~kmin);
   const uint32_t differ = kmax ^ kmin;
   uint32_t t = kmax;                            // all candidates equal: ties only
   if (differ != 0) {
@@ -87,8 +84,7 @@ __global__ __launch_bounds__(256) void select_kernel(
       const uint32_t probe = t | (1u << bit);
       int cnt = 0;
 #pragma unroll
-      for (int c = 0; c < SLOTS; ++c)
-        if (c < slots) cnt += popc64(__ballot(key[c] >= probe));
+      for (int c = 0; c < SLOTS; ++c) cnt += popc64(__ballot(key[c] >= probe));
       if (cnt == want) {
         t = probe - 1;                          // keys > t are exactly the `want` keys >= probe
         break;
@@ -98,25 +94,68 @@ __global__ __launch_bounds__(256) void select_kernel(
   }
   int above = 0;
 #pragma unroll
-  for (int c = 0; c < SLOTS; ++c)
-    if (c < slots) above += popc64(__ballot(key[c] > t));
+  for (int c = 0; c < SLOTS; ++c) above += popc64(__ballot(key[c] > t));
   const int ties_wanted = want - above;         // >= 1 by construction of t
 
   const uint64_t below_me = (uint64_t(1) << lane) - 1;
   int written = 0, ties_seen = 0;
+  int at_least = 0;
 #pragma unroll
-  for (int c = 0; c < SLOTS; ++c) {
-    if (c < slots) {
-      const bool is_tie = key[c] == t;
-      const uint64_t tie_mask = __ballot(is_tie);
-      const int tie_rank = ties_seen + popc64(tie_mask & below_me);
-      const bool take = key[c] > t || (is_tie && tie_rank < ties_wanted);
+  for (int c = 0; c < SLOTS; ++c) at_least += popc64(__ballot(key[c] >= t));
+  if (at_least == want) {                       // every key equal to t is wanted (the usual case: no surplus ties)
+#pragma unroll
+    for (int c = 0; c < SLOTS; ++c) {
+      const bool take = key[c] >= t;
       const uint64_t take_mask = __ballot(take);
       if (take) out[1 + written + popc64(take_mask & below_me)] = c * 64 + lane;
       written += popc64(take_mask);
-      ties_seen += popc64(tie_mask);
     }
+    return;
   }
+#pragma unroll
+  for (int c = 0; c < SLOTS; ++c) {
+    const bool is_tie = key[c] == t;
+    const uint64_t tie_mask = __ballot(is_tie);
+    const int tie_rank = ties_seen + popc64(tie_mask & below_me);
+    const bool take = key[c] > t || (is_tie && tie_rank < ties_wanted);
+    const uint64_t take_mask = __ballot(take);
+    if (take) out[1 + written + popc64(take_mask & below_me)] = c * 64 + lane;
+    written += popc64(take_mask);
+    ties_seen += popc64(tie_mask);
+  }
+}
+
+// One wavefront per row; MAX_SLOTS * 64 >= number of blocks of the longest sequence.
+template <int MAX_SLOTS>
+__global__ __launch_bounds__(256) void select_kernel(
+    SeqMeta meta, const float* __restrict__ scores, const int64_t* __restrict__ sel_ptr,
+    int32_t* __restrict__ sel_idx, int32_t rows) {
+  const int lane = threadIdx.x & 63;
+  // everything that depends only on the row is the same in all lanes: said explicitly, so that it
+  // lives in scalar registers and the branches on it are plain branches, not lane masks
+  const int row = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (row >= rows) return;
+  int s, h, i, nb;
+  decode_row(meta, row, s, h, i, nb);
+  const int64_t begin = sel_ptr[row];
+  int n = __builtin_amdgcn_readfirstlane(int(sel_ptr[row + 1] - begin));
+  n = min(n, i + 1);                            // never more than the causal-visible blocks
+  if (n <= 0) return;
+  int32_t* out = sel_idx + begin;
+  if (lane == 0) {
+    out[0] = 0;
+    if (n >= 2) out[n - 1] = i;
+  }
+  const int want = n - 2;                       // picks among candidates 1..i-1
+  if (want <= 0) return;
+  const float* srow = scores + meta.score_off[s] + (int64_t(h) * nb + i) * nb;
+  const int slots = (i + 63) >> 6;              // slots that hold at least one candidate
+  if (slots <= 2) select_row<2>(srow, out, i, want, lane);
+  else if (slots <= 4) select_row<4>(srow, out, i, want, lane);
+  else if (slots <= 8) select_row<8>(srow, out, i, want, lane);
+  else if (MAX_SLOTS <= 16 || slots <= 16) select_row<16>(srow, out, i, want, lane);
+  else if (slots <= 32) select_row<(MAX_SLOTS > 16 ? 32 : 16)>(srow, out, i, want, lane);
+  else select_row<MAX_SLOTS>(srow, out, i, want, lane);
 }
 
 }  // namespace
