@@ -10,7 +10,8 @@ every part's share is run on this GPU through the whole hot path and the maximum
 Units of the assignment are query heads, as in Section 3.3: cost of a head = its causal block cost
 under the layer's budgets; "naive" gives every part the same number of consecutive heads, "greedy"
 is shplb_balance_heads (parts may end up with different head counts).  A part's share is run with
-the K/V head of each of its query heads (a part holds the KV heads its query heads need).  Inputs
+the distinct KV heads its query heads need, shared among them as in the layer (an explicit query-head
+to KV-head map, since a part's groups need not be whole).  Inputs
 are the synthetic 128K layer of the benchmark (workload cfg2) and shorter contexts of the same
 recipe.  Prints one table; `--json` adds one JSON line per row.
 
@@ -30,16 +31,10 @@ def head_costs(budgets, nb):
 
 
 def share_of(layer, heads):
-    """The part of a layer's workload that a GPU holding `heads` works on."""
-    from workloads import Workload
-    g = layer.n_q_heads // layer.n_kv_heads
-    kv = [h // g for h in heads]
-    budgets = layer.budgets.reshape(layer.n_seq, layer.n_q_heads)[:, heads]
-    return Workload(name=layer.name + "_share", seed=layer.seed, cu_seqlens=layer.cu_seqlens,
-                    n_q_heads=len(heads), n_kv_heads=len(heads), head_dim=layer.head_dim, block=layer.block,
-                    q=np.ascontiguousarray(layer.q[:, heads]), k=np.ascontiguousarray(layer.k[:, kv]),
-                    v=np.ascontiguousarray(layer.v[:, kv]), budgets=np.ascontiguousarray(budgets.reshape(-1)),
-                    meta=dict(layer_heads=list(heads)))
+    """The part of a layer's workload that a GPU holding `heads` works on: those query heads and the
+    distinct KV heads they read, each held once (the part's query heads share them as in the layer)."""
+    from workloads import take_heads
+    return take_heads(layer, heads)
 
 
 def run_share(S, torch, wl, steps, warmup):
@@ -48,7 +43,7 @@ def run_share(S, torch, wl, steps, warmup):
     dev = "cuda:0"
     to_dev = lambda b: torch.from_numpy(b.view(np.int16)).to(dev).view(torch.bfloat16)
     q, k, v = to_dev(wl.q), to_dev(wl.k), to_dev(wl.v)
-    p = S.Problem(wl.cu_seqlens, wl.n_q_heads, wl.n_kv_heads, wl.block, wl.head_dim)
+    p = S.Problem(wl.cu_seqlens, wl.n_q_heads, wl.n_kv_heads, wl.block, wl.head_dim, kv_head_of=wl.kv_head_of)
     ws = torch.empty(S.shplb_workspace_bytes(p), dtype=torch.uint8, device=dev)
     scores = torch.empty(int(S.shplb_score_layout(p)[-1]), dtype=torch.float32, device=dev)
     sel_ptr_h = S.shplb_sel_row_ptr(p, wl.budgets)
@@ -74,6 +69,26 @@ def run_share(S, torch, wl, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def ablation_case(S, seqlen, degree, n_heads, part_ms):
+    """One row of the ablation: consecutive heads against shplb_balance_heads for one context length and
+    parallelism degree.  part_ms(seqlen, heads) -> ms of the whole hot path over that part's share."""
+    from workloads import layer_budgets
+    lb = layer_budgets(2, [seqlen])
+    cost = head_costs(lb["budgets"][0], lb["n_blocks"][0])
+    per = n_heads // degree
+    naive = [list(range(d * per, (d + 1) * per)) for d in range(degree)]
+    part_of, _ = S.shplb_balance_heads(cost, degree)
+    greedy = [[x for x in range(n_heads) if part_of[x] == d] for d in range(degree)]
+    rec = {"tokens": seqlen, "degree": degree}
+    for name, parts in (("naive", naive), ("greedy", greedy)):
+        loads = [int(cost[p].sum()) for p in parts]
+        ms = [part_ms(seqlen, p) for p in parts]
+        rec[name] = {"parts": parts, "cost_imbalance": max(loads) / (sum(loads) / degree),
+                     "part_ms": ms, "layer_ms": max(ms)}
+    rec["speedup"] = rec["naive"]["layer_ms"] / rec["greedy"]["layer_ms"]
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--steps", type=int, default=3)
@@ -83,7 +98,7 @@ def main():
 
     import torch
     import paper_2603_10353_amd as S
-    from workloads import CONFIGS, layer_budgets, make_workload
+    from workloads import CONFIGS, make_workload
     torch.cuda.set_device(0)
 
     n_heads = CONFIGS[2]["n_q_heads"]
@@ -101,22 +116,7 @@ def main():
                   flush=True)
         return latency[key]
 
-    rows = []
-    for seqlen, degree in sorted(cases):
-        lb = layer_budgets(2, [seqlen])
-        cost = head_costs(lb["budgets"][0], lb["n_blocks"][0])
-        per = n_heads // degree
-        naive = [list(range(d * per, (d + 1) * per)) for d in range(degree)]
-        part_of, _ = S.shplb_balance_heads(cost, degree)
-        greedy = [[x for x in range(n_heads) if part_of[x] == d] for d in range(degree)]
-        rec = {"tokens": seqlen, "degree": degree}
-        for name, parts in (("naive", naive), ("greedy", greedy)):
-            loads = [int(cost[p].sum()) for p in parts]
-            ms = [part_ms(seqlen, p) for p in parts]
-            rec[name] = {"parts": parts, "cost_imbalance": max(loads) / (sum(loads) / degree),
-                         "part_ms": ms, "layer_ms": max(ms)}
-        rec["speedup"] = rec["naive"]["layer_ms"] / rec["greedy"]["layer_ms"]
-        rows.append(rec)
+    rows = [ablation_case(S, seqlen, degree, n_heads, part_ms) for seqlen, degree in sorted(cases)]
 
     print("%8s %6s | %-22s | %-22s | %s" % ("tokens", "degree", "naive: I(cost)  ms", "greedy: I(cost)  ms", "naive/greedy"))
     for r in rows:

@@ -33,6 +33,11 @@
  *   - Row index of (sequence s, query head h, query block i):
  *       row = (sum_{s'<s} nb_s') * n_q_heads + h * nb_s + i.
  *   - GQA: query head h reads KV head h / (n_q_heads / n_kv_heads) (Section 2.1).
+ *     A GPU's share under the head-to-device assignment of Section 3.3 is an
+ *     arbitrary set of query heads, so its heads need not form whole groups of equal
+ *     size: kv_head_of, when not NULL, gives the KV head (0 .. n_kv_heads-1, among
+ *     the KV heads this call is given) of every query head, and n_q_heads need not
+ *     be a multiple of n_kv_heads (both at most SHPLB_MAX_MAPPED_HEADS then).
  */
 #ifndef SHPLB_H
 #define SHPLB_H
@@ -56,16 +61,18 @@ extern "C" {
 #define SHPLB_MAX_SEQ        64    /* sequences per call */
 #define SHPLB_MAX_BLOCKS   4096    /* blocks per sequence */
 #define SHPLB_MAX_SEQ_HEADS 65535  /* n_seq * n_q_heads per call */
+#define SHPLB_MAX_MAPPED_HEADS 256  /* n_q_heads and n_kv_heads with an explicit kv_head_of */
 
 typedef struct {
   int32_t n_seq;                 /* 1..SHPLB_MAX_SEQ */
   const int32_t* cu_seqlens;     /* host [n_seq+1]; cu[0] = 0, strictly increasing */
-  int32_t n_q_heads, n_kv_heads; /* n_q_heads % n_kv_heads == 0 */
+  int32_t n_q_heads, n_kv_heads; /* n_q_heads % n_kv_heads == 0 unless kv_head_of is given */
   int32_t head_dim;              /* 128 */
   int32_t block;                 /* 64 or 128 */
   int64_t q_stride_t, q_stride_h;   /* element strides of Q (and of the output O) */
   int64_t kv_stride_t, kv_stride_h; /* element strides of K and V */
   float softmax_scale;           /* > 0, or 0 for 1/sqrt(head_dim) (Eq. 1) */
+  const int32_t* kv_head_of;     /* host [n_q_heads], or NULL: see below */
 } shplb_problem;
 
 /* Per-workgroup record written by shplb_sparse_attn_prefill when asked for. */

@@ -38,6 +38,7 @@ class _CProblem(C.Structure):
         ("kv_stride_t", C.c_int64),
         ("kv_stride_h", C.c_int64),
         ("softmax_scale", C.c_float),
+        ("kv_head_of", C.POINTER(C.c_int32)),
     ]
 
 
@@ -101,20 +102,24 @@ def load_library():
 
 
 class Problem:
-    """Host-side mirror of the C struct shplb_problem (keeps cu_seqlens alive)."""
+    """Host-side mirror of the C struct shplb_problem (keeps cu_seqlens and kv_head_of alive)."""
 
     def __init__(self, cu_seqlens: Sequence[int], n_q_heads: int, n_kv_heads: int, block: int,
                  head_dim: int = 128, q_stride_t: Optional[int] = None, q_stride_h: Optional[int] = None,
                  kv_stride_t: Optional[int] = None, kv_stride_h: Optional[int] = None,
-                 softmax_scale: float = 0.0):
+                 softmax_scale: float = 0.0, kv_head_of: Optional[Sequence[int]] = None):
         self.cu = np.ascontiguousarray(np.asarray(cu_seqlens, dtype=np.int32))
+        self.kv_head_of = None if kv_head_of is None else np.ascontiguousarray(np.asarray(kv_head_of, dtype=np.int32))
+        if self.kv_head_of is not None and self.kv_head_of.size != n_q_heads:
+            raise ValueError("kv_head_of must hold n_q_heads entries")
         q_stride_h = head_dim if q_stride_h is None else q_stride_h
         kv_stride_h = head_dim if kv_stride_h is None else kv_stride_h
         q_stride_t = n_q_heads * q_stride_h if q_stride_t is None else q_stride_t
         kv_stride_t = n_kv_heads * kv_stride_h if kv_stride_t is None else kv_stride_t
         self.c = _CProblem(len(self.cu) - 1, self.cu.ctypes.data_as(C.POINTER(C.c_int32)),
                            n_q_heads, n_kv_heads, head_dim, block, q_stride_t, q_stride_h,
-                           kv_stride_t, kv_stride_h, softmax_scale)
+                           kv_stride_t, kv_stride_h, softmax_scale,
+                           None if self.kv_head_of is None else self.kv_head_of.ctypes.data_as(C.POINTER(C.c_int32)))
 
     @property
     def n_seq(self) -> int:

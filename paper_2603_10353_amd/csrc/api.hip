@@ -20,7 +20,13 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g) {
   if (p->n_seq > SHPLB_MAX_SEQ) return SHPLB_E_UNSUPPORTED;
   // (sequence, head) pairs index the z dimension of the scoring grid
   if (int64_t(p->n_seq) * p->n_q_heads > SHPLB_MAX_SEQ_HEADS) return SHPLB_E_UNSUPPORTED;
-  if (p->n_q_heads % p->n_kv_heads) return SHPLB_E_SHAPE;
+  if (p->kv_head_of == nullptr) {
+    if (p->n_q_heads % p->n_kv_heads) return SHPLB_E_SHAPE;
+  } else {
+    if (p->n_q_heads > SHPLB_MAX_MAPPED_HEADS || p->n_kv_heads > SHPLB_MAX_MAPPED_HEADS) return SHPLB_E_UNSUPPORTED;
+    for (int h = 0; h < p->n_q_heads; ++h)
+      if (p->kv_head_of[h] < 0 || p->kv_head_of[h] >= p->n_kv_heads) return SHPLB_E_SHAPE;
+  }
   if (p->head_dim != kHeadDim) return SHPLB_E_UNSUPPORTED;
   if (p->block != 64 && p->block != 128) return SHPLB_E_UNSUPPORTED;
   if (p->cu_seqlens[0] != 0) return SHPLB_E_SHAPE;
@@ -38,6 +44,8 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g) {
   m.n_q_heads = p->n_q_heads;
   m.n_kv_heads = p->n_kv_heads;
   m.block = p->block;
+  m.kv_map = p->kv_head_of != nullptr;
+  for (int h = 0; m.kv_map && h < p->n_q_heads; ++h) m.kv_of[h] = uint8_t(p->kv_head_of[h]);
   int64_t score_off = 0;
   int32_t max_nb = 0;
   for (int s = 0; s < p->n_seq; ++s) {

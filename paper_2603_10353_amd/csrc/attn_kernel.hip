@@ -50,7 +50,6 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hi = lane >> 5;
-  const int group = meta.n_q_heads / meta.n_kv_heads;
 
   // ---- per-lane constants
   // global->LDS copies: lane (r4 = lane>>4, slot = lane&15) of a wave fills LDS row
@@ -93,7 +92,7 @@ void attn_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     if (row < 0 || row >= meta.blk_begin[meta.n_seq] * meta.n_q_heads || slot >= sb.slot_capacity) continue;
     int s, h, i, nb;
     decode_row(meta, row, s, h, i, nb);
-    const int g = h / group;
+    const int g = kv_head_of(meta, h);
     const int seq_begin = meta.tok_begin[s], seq_end = meta.tok_begin[s + 1];
     const int n_tiles = n_sel * SUB;
     if (n_sel <= 0) continue;          // malformed row: nothing to attend to

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(2 * BQ) void mass_kernel(SeqMeta meta, Strides st, 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hi = lane >> 5;
-  const int g = h / (meta.n_q_heads / meta.n_kv_heads);
+  const int g = kv_head_of(meta, h);
   const int seq_begin = meta.tok_begin[s], seq_end = meta.tok_begin[s + 1];
   const int n_tiles = (i + 1) * SUB;
   const int64_t row_bytes = st.kv_t * 2;

@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hi = lane >> 5;
-  const int g = h / (meta.n_q_heads / meta.n_kv_heads);
+  const int g = kv_head_of(meta, h);
   const int i_first = ti + 32 * wave;               // this wave's rows
   const int i_last = min(ti + kScoreTile, nb) - 1;  // last row of the workgroup
   const int n_jt = (min(tj + chunk, i_last + 1) - tj + kScoreJ - 1) / kScoreJ;   // 32-row K tiles with some j <= i

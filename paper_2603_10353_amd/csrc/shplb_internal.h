@@ -29,6 +29,8 @@ struct SeqMeta {
   int32_t tok_begin[SHPLB_MAX_SEQ + 1];   // cu_seqlens
   int32_t blk_begin[SHPLB_MAX_SEQ + 1];   // cumulative block counts
   int64_t score_off[SHPLB_MAX_SEQ + 1];   // float offset of each sequence's score cube
+  int32_t kv_map;                         // 1: kv_of[] holds the KV head of every query head
+  uint8_t kv_of[SHPLB_MAX_MAPPED_HEADS];
 };
 
 struct Strides {
@@ -148,6 +150,11 @@ void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, c
                               shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg,
                               hipStream_t stream);
 
+// KV head that query head h reads: the caller's map, or equal groups of consecutive heads.
+__device__ __forceinline__ int kv_head_of(const SeqMeta& m, int h) {
+  return m.kv_map ? int(m.kv_of[h]) : h / (m.n_q_heads / m.n_kv_heads);
+}
+
 // Row -> (sequence, head, query block).  Rows of one sequence are contiguous.
 __device__ __forceinline__ void decode_row(const SeqMeta& m, int32_t row, int& s, int& h, int& i, int& nb) {
   s = 0;
@@ -164,7 +171,7 @@ __device__ __forceinline__ void decode_row(const SeqMeta& m, int32_t row, int& s
 __device__ __forceinline__ int xcd_of_row(const SeqMeta& m, int32_t row) {
   int s, h, i, nb;
   decode_row(m, row, s, h, i, nb);
-  const int stream = s * m.n_kv_heads + h / (m.n_q_heads / m.n_kv_heads);
+  const int stream = s * m.n_kv_heads + kv_head_of(m, h);
   const int n_streams = m.n_seq * m.n_kv_heads;
   if (n_streams >= kXcds) return stream % kXcds;
   const int per = kXcds / n_streams;

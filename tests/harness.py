@@ -10,7 +10,7 @@ from paper_2603_10353_amd.binding import WG_STATS_DTYPE
 
 def problem_of(wl, softmax_scale: float = 0.0) -> S.Problem:
     return S.Problem(wl.cu_seqlens, wl.n_q_heads, wl.n_kv_heads, wl.block, wl.head_dim,
-                     softmax_scale=softmax_scale)
+                     softmax_scale=softmax_scale, kv_head_of=wl.kv_head_of)
 
 
 def to_dev_bf16(bits: np.ndarray) -> torch.Tensor:

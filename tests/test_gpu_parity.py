@@ -22,6 +22,10 @@ def full_parity(wl, softmax_scale=0.0, rows=None):
     print("case", wl.name, "seqlens", np.diff(wl.cu_seqlens).tolist(), "heads", wl.n_q_heads, wl.n_kv_heads,
           "block", wl.block, "budgets", wl.budgets.tolist()[:16], flush=True)
     run = _gpu()(wl, softmax_scale).run_all()
+    if wl.kv_head_of is not None:
+        # the oracle knows equal groups only: it gets every query head's K/V head as a head of its own
+        from workloads import one_kv_head_per_query_head
+        wl = one_kv_head_per_query_head(wl)
     scale = None if softmax_scale == 0.0 else softmax_scale
     sc_o = orc.block_scores(wl.q, wl.k, wl.cu_seqlens, wl.block, scale)
     sc_g = run.scores_host()
@@ -245,6 +249,24 @@ def test_whole_path_in_a_hip_graph():
         assert torch.equal(run.sel_idx, ref[1]), replay
         assert torch.equal(run.out.view(torch.int16), ref[2].view(torch.int16)), replay
         assert torch.equal(run.lse, ref[3]), replay
+
+
+@pytest.mark.parametrize("block", [64, 128])
+def test_irregular_share_of_heads(block):
+    # A device's share under the head-to-device assignment: query heads 0, 3, 4, 5, 7, 9 of a 12/4-head
+    # layer (groups of 3) read KV heads 0, 1, 1, 1, 2, 3 -- groups of 1, 3, 1 and 1 heads, which only an
+    # explicit map can express.  Two ragged sequences.
+    from workloads import take_heads
+    layer = make_custom([block * 9 + 31, block * 3 + 2], 12, 4, block, [2, 999, 5, 3, 7, 4, 999, 2, 6, 5, 3, 8] * 2,
+                        seed=97, name="layer12")
+    share = take_heads(layer, [0, 3, 4, 5, 7, 9])
+    assert share.kv_head_of.tolist() == [0, 1, 1, 1, 2, 3] and share.n_kv_heads == 4
+    run = full_parity(share)
+    # the shared run must agree bit for bit with the same heads run with private K/V copies
+    from workloads import one_kv_head_per_query_head
+    ref = _gpu()(one_kv_head_per_query_head(share)).run_all()
+    assert torch.equal(run.out.view(torch.int16), ref.out.view(torch.int16)) and torch.equal(run.lse, ref.lse)
+    assert torch.equal(run.sel_idx, ref.sel_idx)
 
 
 def test_explicit_softmax_scale():

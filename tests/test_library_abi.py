@@ -30,7 +30,7 @@ def test_exports_match_header(repo_root):
 
 def test_struct_layout_matches_header():
     from paper_2603_10353_amd.binding import _CProblem, WgStats
-    assert C.sizeof(_CProblem) == 72 and _CProblem.softmax_scale.offset == 64
+    assert C.sizeof(_CProblem) == 80 and _CProblem.softmax_scale.offset == 64 and _CProblem.kv_head_of.offset == 72
     assert C.sizeof(WgStats) == 32
 
 
@@ -97,6 +97,18 @@ def test_argument_validation():
         S.shplb_sparse_attn_prefill_split(p, None, None, None, None, None, None, split_slots=64)
     assert e.value.status == -1
     assert "null" in S.shplb_strerror(-1) and S.shplb_strerror(0) == "ok"
+    # an explicit query-head -> KV-head map lifts the divisibility rule and is range-checked
+    assert S.shplb_num_rows(S.Problem([0, 1000], 5, 2, 128, kv_head_of=[0, 0, 1, 0, 1])) == 5 * 8
+    for bad in ([0, 0, 2, 0, 1], [0, -1, 1, 0, 1]):
+        with pytest.raises(S.ShplbError) as e:
+            S.shplb_num_rows(S.Problem([0, 1000], 5, 2, 128, kv_head_of=bad))
+        assert e.value.status == -2
+    with pytest.raises(S.ShplbError) as e:
+        S.shplb_num_rows(S.Problem([0, 1000], 300, 2, 128, kv_head_of=[0] * 300))
+    assert e.value.status == -5
+    with pytest.raises(S.ShplbError) as e:
+        S.shplb_num_rows(S.Problem([0, 1000], 5, 2, 128))           # no map: 5 heads do not divide into 2 groups
+    assert e.value.status == -2
 
 
 @pytest.mark.parametrize("seed", range(8))

@@ -13,4 +13,6 @@ from .synth import (  # noqa: F401
     layer_budgets,
     make_workload,
     make_custom,
+    one_kv_head_per_query_head,
+    take_heads,
 )

@@ -67,6 +67,7 @@ class Workload:
     v: np.ndarray                   # uint16 (bf16 bits) [T, n_kv_heads, head_dim]
     budgets: np.ndarray             # int32 [n_seq * n_q_heads], in key blocks
     meta: dict = field(default_factory=dict)
+    kv_head_of: Optional[np.ndarray] = None   # int32 [n_q_heads]: KV head of each query head; None = equal groups
 
     @property
     def n_seq(self) -> int:
@@ -244,3 +245,39 @@ def _materialise(name, seed, seqlens, hq, hkv, blk, c_range, budgets, extra) -> 
     return Workload(name=name, seed=seed, cu_seqlens=cu, n_q_heads=hq, n_kv_heads=hkv, head_dim=d,
                     block=blk, q=q, k=k, v=v, budgets=np.ascontiguousarray(budgets.reshape(-1), np.int32),
                     meta=meta)
+
+
+def take_heads(wl: Workload, heads: Sequence[int]) -> Workload:
+    """The share of a layer that a device holding the query heads `heads` works on: their Q
+    columns and budgets, and the distinct KV heads they read (each once), with the map from
+    the share's query heads to its KV heads.  Any subset in any order: the groups of a share
+    need not be whole or of equal size.  Slicing only."""
+    heads = [int(h) for h in heads]
+    if wl.kv_head_of is None:
+        g = wl.n_q_heads // wl.n_kv_heads
+        kv_of_layer = [h // g for h in range(wl.n_q_heads)]
+    else:
+        kv_of_layer = [int(x) for x in wl.kv_head_of]
+    kv = sorted({kv_of_layer[h] for h in heads})
+    local = {x: n for n, x in enumerate(kv)}
+    budgets = wl.budgets.reshape(wl.n_seq, wl.n_q_heads)[:, heads]
+    meta = dict(layer_heads=heads, layer_kv_heads=kv)
+    return Workload(name=wl.name + "_heads_" + "_".join(map(str, heads)), seed=wl.seed, cu_seqlens=wl.cu_seqlens,
+                    n_q_heads=len(heads), n_kv_heads=len(kv), head_dim=wl.head_dim, block=wl.block,
+                    q=np.ascontiguousarray(wl.q[:, heads]), k=np.ascontiguousarray(wl.k[:, kv]),
+                    v=np.ascontiguousarray(wl.v[:, kv]), budgets=np.ascontiguousarray(budgets.reshape(-1)),
+                    meta=meta, kv_head_of=np.asarray([local[kv_of_layer[h]] for h in heads], np.int32))
+
+
+def one_kv_head_per_query_head(wl: Workload) -> Workload:
+    """The same inputs with every query head given its own copy of the K/V head it reads (no
+    sharing, no map): what a reference that only knows equal groups can be fed.  Slicing only."""
+    if wl.kv_head_of is None:
+        g = wl.n_q_heads // wl.n_kv_heads
+        kv = [h // g for h in range(wl.n_q_heads)]
+    else:
+        kv = [int(x) for x in wl.kv_head_of]
+    return Workload(name=wl.name + "_unshared", seed=wl.seed, cu_seqlens=wl.cu_seqlens, n_q_heads=wl.n_q_heads,
+                    n_kv_heads=wl.n_q_heads, head_dim=wl.head_dim, block=wl.block, q=wl.q,
+                    k=np.ascontiguousarray(wl.k[:, kv]), v=np.ascontiguousarray(wl.v[:, kv]), budgets=wl.budgets,
+                    meta=dict(wl.meta))
