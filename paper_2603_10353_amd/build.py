@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD = os.path.join(PKG_DIR, "_build")
 LIB = os.path.join(PKG_DIR, "libshplb.so")
-SOURCES = ["api.hip", "score_kernels.hip", "select_kernel.hip", "sched_kernels.hip", "attn_kernel.hip",
+SOURCES = ["api.hip", "score_kernels.hip", "select_kernel.hip", "sched_kernels.hip",
            "attn_pipe_kernel.hip", "profile_kernel.hip", "probe_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-fno-honor-nans",

@@ -45,7 +45,7 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g) {
   m.n_kv_heads = p->n_kv_heads;
   m.block = p->block;
   m.kv_map = p->kv_head_of != nullptr;
-  for (int h = 0; m.kv_map && h < p->n_q_heads; ++h) m.kv_of[h] = uint8_t(p->kv_head_of[h]);
+  for (int h = 0; m.kv_map && h < p->n_q_heads; ++h) m.kv_of[h >> 2] |= uint32_t(p->kv_head_of[h]) << (8 * (h & 3));
   int64_t score_off = 0;
   int32_t max_nb = 0;
   for (int s = 0; s < p->n_seq; ++s) {
@@ -96,7 +96,7 @@ WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots, bool with_po
   return w;
 }
 
-int32_t persistent_workgroups() {
+int32_t persistent_workgroups(int block) {
   static int cached[64] = {0};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return SHPLB_E_HIP;
@@ -105,9 +105,10 @@ int32_t persistent_workgroups() {
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
       return SHPLB_E_HIP;
-    cached[dev] = cus * 2;   // two workgroups per compute unit (two waves per SIMD)
+    cached[dev] = cus;
   }
-  return cached[dev];
+  // two waves per SIMD: two 4-wave workgroups (128-token blocks) or four 2-wave ones (64) per compute unit
+  return cached[dev] * (block == 64 ? 4 : 2);
 }
 
 }  // namespace shplb
@@ -202,7 +203,7 @@ int32_t shplb_sched_num_workgroups(const shplb_problem* p, int32_t* n_out) {
   if (!n_out) return SHPLB_E_NULL;
   Geometry g;
   if (int32_t st = make_geometry(p, &g)) return st;
-  const int32_t n = persistent_workgroups();
+  const int32_t n = persistent_workgroups(g.meta.block);
   if (n < 0) return n;
   *n_out = n;
   return SHPLB_OK;
@@ -253,7 +254,7 @@ int32_t attention_entry(const shplb_problem* p, const void* q, const void* k, co
        reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(out)) & 15)
     return SHPLB_E_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return SHPLB_E_SHAPE;
-  const int32_t n_wg = persistent_workgroups();
+  const int32_t n_wg = persistent_workgroups(g.meta.block);
   if (n_wg < 0) return n_wg;
   const WorkspaceLayout w = make_layout(g, split_slots, !static_scratch_call);
   char* ws = static_cast<char*>(workspace);

@@ -119,40 +119,48 @@ __device__ __forceinline__ float slot_load1(const float* p) {
   return __uint_as_float(__hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
 
-// Called by every thread of a workgroup whose item was a piece of a split row, after the piece's
-// partial result went to its slot (slot_store): the unnormalised output O_c, the sum l_c of its
-// probabilities, both relative to a reference exponent m_c (p = 2^(s*scale*log2e - m_c)).  The piece
-// is counted; the piece of a row that is counted last combines all of them.  Softmax over the union
-// of the pieces (Eq. 1 over the selected keys) is, with m = max_c m_c and w_c = 2^(m_c - m),
+// Pieces of split rows.  A piece leaves in its slot (slot_store) the unnormalised output O_c, the sum
+// l_c of its probabilities, both relative to a reference exponent m_c (p = 2^(s*scale*log2e - m_c)),
+// and is then counted (count_piece); the piece of a row that is counted last has the row combined
+// (merge_row).  Softmax over the union of the pieces (Eq. 1 over the selected keys) is, with
+// m = max_c m_c and w_c = 2^(m_c - m),
 //
 //     out = sum_c w_c O_c / sum_c w_c l_c,      lse = (m + log2 sum_c w_c l_c) ln 2,
 //
-// summed in piece order from the slots (the last piece reads its own result back like the
-// others), so the result depends neither on which piece finished last nor on slot numbers.
-// Order: every thread waits until its slot stores are done, the workgroup meets at a barrier, one
-// thread counts the piece with a device-scope atomic; whoever sees the count complete reads the slots
-// (and returns true).
-// The combination runs in two passes so that few dependent memory round trips remain: first one
-// thread per query turns the pieces' (m_c, l_c) into weights w_c / sum w_c l_c in LDS, then every
-// thread accumulates its 16 output chunks piece by piece, the 32 loads of a piece in flight together.
-//   out_row: output of the row's first query (head applied); lse_row: likewise, or null;
-//   n_valid: valid queries of the row (ragged last block); s_flag: one int of LDS;
-//   lds_w, lds_l: kMaxPieces * BQ floats of LDS each that nobody else uses until the workgroup's next barrier.
+// summed in piece order from the slots (the last piece reads its own result back like the others),
+// so the result depends neither on which piece finished last nor on slot numbers.
 constexpr int kMaxPieces = kSplitMaxPieces;
-template <int BQ, int THREADS>
-__device__ __attribute__((noinline)) bool finish_piece(const SplitBuffers& sb, int pieces, int first_slot, int split_index,
-                                                       uint16_t* out_row, int64_t q_stride_t, float* lse_row,
-                                                       int n_valid, int32_t* s_flag, float* lds_w, float* lds_l) {
+constexpr int kDeferredMerges = 1024;   // rows a workgroup can owe a merge (it stops taking items when full)
+
+// Called by every thread of the workgroup after the piece's slot stores were issued.  Every thread
+// waits until its stores are done, the workgroup meets at a barrier, one thread counts the piece with
+// a device-scope atomic.  Returns (to all threads) whether this piece completed its row.
+__device__ __forceinline__ bool count_piece(const SplitBuffers& sb, int pieces, int split_index, int32_t* s_flag) {
   // item records come from the ordering kernels; a malformed one must not index out of bounds
-  if (pieces < 2 || pieces > kMaxPieces || first_slot < 0 || first_slot + pieces > sb.slot_capacity ||
-      split_index < 0 || split_index > sb.slot_capacity / 2)
-    return false;
+  if (pieces < 2 || pieces > kMaxPieces || split_index < 0 || split_index > sb.slot_capacity / 2) return false;
   wait_vmem_all();
   __syncthreads();
   if (threadIdx.x == 0)
     *s_flag = int(__hip_atomic_fetch_add(sb.done + split_index, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
   __syncthreads();
-  if (*s_flag != pieces - 1) return false;
+  return __builtin_amdgcn_readfirstlane(*s_flag) == pieces - 1;
+}
+
+// Combine the pieces of one row into the output.  Two passes, so that few dependent memory round
+// trips remain: first one thread per query turns the pieces' (m_c, l_c) into weights
+// w_c / sum w_c l_c in LDS, then every thread accumulates its 16 output chunks piece by piece, the 16
+// loads of a piece in flight together.  Kept out of line and called when nothing of the attention
+// loop is live any more: inside that loop it cost the loop its register allocation (59 spilled
+// registers against 4).
+//   out_row: output of the row's first query (head applied); lse_row: likewise, or null;
+//   n_valid: valid queries of the row (ragged last block);
+//   lds_w, lds_l: kMaxPieces * BQ floats of LDS each.
+template <int BQ, int THREADS>
+__device__ __attribute__((noinline)) void merge_row(const SplitBuffers& sb, int pieces, int first_slot,
+                                                    uint16_t* out_row, int64_t q_stride_t, float* lse_row,
+                                                    int n_valid, float* lds_w, float* lds_l) {
+  if (pieces < 2 || pieces > kMaxPieces || first_slot < 0 || first_slot + pieces > sb.slot_capacity) return;
+  __syncthreads();                                  // the LDS tables are free (an earlier merge is over)
   const float* part_o = sb.part_o + int64_t(first_slot) * kSlotFloatsO;
   const float* part_ml = sb.part_ml + int64_t(first_slot) * kSlotFloatsML;
   // pass 1: thread q < BQ: weights of the pieces for query q, already divided by the denominator
@@ -181,10 +189,10 @@ __device__ __attribute__((noinline)) bool finish_piece(const SplitBuffers& sb, i
   // chunk e = ((wave * 4 + dt) * 4 + rq) * 64 + lane is dims 32 dt + 8 rq + 4 (lane / 32) .. +3 of query
   // 32 wave + lane % 32.  A thread owns chunks threadIdx.x + THREADS * u; a wave reads 1 KB runs.
   constexpr int kChunks = BQ * (kHeadDim / 4) / THREADS;
+  static_assert(kChunks % 4 == 0, "chunks are awaited four at a time");
   f32x4 acc[kChunks];
 #pragma unroll
   for (int u = 0; u < kChunks; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-  static_assert(kChunks % 4 == 0, "chunks are awaited four at a time");
   for (int c = 0; c < pieces; ++c) {
     f32x4 o[kChunks];
 #pragma unroll
@@ -210,7 +218,6 @@ __device__ __attribute__((noinline)) bool finish_piece(const SplitBuffers& sb, i
     w2.y = pack_bf16(acc[u].z, acc[u].w);
     *reinterpret_cast<u32x2*>(out_row + int64_t(q_in) * q_stride_t + d) = w2;
   }
-  return true;
 }
 
 // Where lane `lane` of wave `wave` keeps its four accumulator values rq of dim tile dt in a slot: the

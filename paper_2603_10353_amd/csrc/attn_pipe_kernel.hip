@@ -1,31 +1,43 @@
-// Software-pipelined block-sparse causal attention for 128-token blocks (gfx950).
+// Software-pipelined block-sparse causal attention over per-row selected key blocks (gfx950).
 //
-// Same data layout as attn_kernel.hip (64-key tiles, S^T = K Q^T then O^T += V^T P^T,
-// swizzled 256-byte LDS rows filled by direct global->LDS copies).  What differs:
+// Work item = one (sequence, head, query block) row of the selection, or a piece of one.
+// Persistent workgroups draw items from cost-descending queues through atomic tickets.
 //
-//   * a wave owns 32*NT query rows.  The library builds NT = 1: four waves of 32 rows, two
-//     workgroups per compute unit, so each SIMD holds two waves of different workgroups
-//     and a wave has 256 registers.  NT = 2 (64 rows per wave, every LDS operand feeding
-//     two MFMAs, one 512-register wave per SIMD) compiles, but the compiler cannot keep
-//     its accumulators in place and moves hundreds of them per tile: it is not used;
-//   * the order of work inside a wave.  A step handles tile t's softmax and second
-//     contraction and tile t+1's first contraction:
+// Tiling (wave64, v_mfma_f32_32x32x16_bf16), for blocks of BQ = 128 or 64 tokens:
+//   * a wave owns 32 query rows and keeps Q as MFMA B-operands in registers; a query block is
+//     BQ/32 waves.  Block 128: 4 waves, two workgroups per compute unit; block 64: 2 waves, four
+//     workgroups per compute unit.  Either way every SIMD holds two waves of different
+//     workgroups, each with 256 registers, and one wave's softmax VALU work overlaps the other's
+//     MFMAs;
+//   * keys are streamed in tiles of KT = BQ/2 keys, two tiles per key block.  K and V rows go
+//     from global memory straight into a double-buffered LDS stage (global_load_lds_dwordx4, no
+//     staging registers, no LDS store instructions).  Rows are 256 bytes, unpadded; the 16-byte
+//     chunk c of row r sits at chunk slot c ^ swz(r), which keeps both the K operand reads and
+//     the V transpose reads free of bank conflicts;
+//   * the first contraction is S^T = K Q^T (A = K from LDS by 16-byte reads), so a lane holds one
+//     query column: the softmax max/sum are in-lane plus one exchange with lane^32, and the
+//     probabilities feed the second contraction O^T += V^T P^T straight from registers (the key
+//     order inside a 16-key MFMA step is permuted identically on both operands, which a sum over
+//     keys does not see); V^T operands come from the LDS transpose read (ds_read_b64_tr_b16);
+//   * the order of work inside a wave.  A step handles tile t's softmax and second contraction
+//     and tile t+1's first contraction:
 //
 //       step t:  barrier                      K(t+1), V(t) resident; stages of K(t), V(t-1) free
 //                copies K(t+2), V(t+1) start
-//                16 MFMAs of S(t+1), back to back; mask S(t+1) if it is the diagonal block
-//                exp / bf16 pack / row sum of the 32 probabilities of tile t (one run of VALU work);
+//                the MFMAs of S(t+1), back to back; mask S(t+1) if it is the diagonal block
+//                exp / bf16 pack / row sum of the probabilities of tile t (one run of VALU work);
 //                if a row sum shows that the reference maximum was too low (rare): true
 //                maximum of the tile, rescale O and l, probabilities again
-//                16 MFMAs of O += V(t)^T P(t)^T, back to back
+//                the MFMAs of O += V(t)^T P(t)^T, back to back
 //
 //     so a wave alternates between blocks of MFMAs and a block of VALU work that depends
 //     on none of the MFMAs in flight, and the two waves of a SIMD (of different workgroups,
-//     unsynchronised) mostly find the other unit free;
+//     unsynchronised) mostly find the other unit free.
 //
 // The two score buffers swap roles from step to step (the tile count is even, steps are
 // issued in pairs).  LDS operands are fetched kLook groups ahead of their use.  Fully
 // masked sub-tiles are computed like any other (their probabilities are exact zeros).
+// With 64-token blocks a tile feeds half as many MFMAs per copy, barrier and item as with 128.
 #include <type_traits>
 
 #include "attn_common.h"
@@ -33,35 +45,47 @@
 namespace shplb {
 namespace {
 
-template <int NT>
-__global__ __launch_bounds__(256 / NT) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 2 : 1, NT == 1 ? 2 : 1)))
+template <int BQ>
+__global__ __launch_bounds__(2 * BQ) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
                       const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                       const int64_t* __restrict__ sel_ptr, const int32_t* __restrict__ sel_idx,
                       uint16_t* __restrict__ out, float* __restrict__ lse,
                       shplb_wg_stats* __restrict__ stats, WorkQueues wq, SplitBuffers sb, int64_t total_tokens,
                       float scale_log2) {
-  constexpr int BQ = 128;
-  constexpr int kWaves = 4 / NT;
-  constexpr int QW = 32 * NT;                        // query rows per wave
+  constexpr int NT = 1;                              // 32-query tiles per wave
+  constexpr int kWaves = BQ / 32;
+  constexpr int QW = 32;                             // query rows per wave
+  constexpr int KT = BQ / 2;                         // keys per tile: two tiles per key block
+  constexpr int MT = KT / 32;                        // 32-key MFMA tiles of a tile's scores
+  constexpr int kTileBytes = KT * kRowBytes;
   constexpr int kRoundRows = 4 * kWaves;             // rows one round of copies moves (4 per wave)
-  constexpr int kRounds = kKeysPerTile / kRoundRows;
+  constexpr int kRounds = KT / kRoundRows;
+  constexpr int kQK = 8 * MT;                        // MFMAs of a tile's first contraction, index 2*ks + mt (MT = 2) or ks
+  constexpr int kPV = 4 * (KT / 16);                 // ... of its second, index 4*gq + dt
   constexpr int kLook = 8;             // LDS operand fetches run this many groups ahead
+  constexpr float kSumLimit = 16.0f * MT * 256.0f;   // a lane's 16 MT probabilities of a tile can only sum to
+                                                     // more if one of them exceeds 2^8
 
   __shared__ __attribute__((aligned(1024))) char k_lds[2][kTileBytes];
   __shared__ __attribute__((aligned(1024))) char v_lds[2][kTileBytes];
   __shared__ int32_t s_item;
   __shared__ int32_t s_flag;
+  __shared__ int32_t s_merge[kDeferredMerges];   // items whose row this workgroup still has to combine
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hi = lane >> 5;
   const int64_t row_bytes = st.kv_t * 2;
 
-  // ---- per-lane constants (see attn_kernel.hip for the layouts)
-  // copies: in round rd this lane fills LDS row rd*kRoundRows + cp_row, slot lane&15, with
-  // source chunk slot ^ swz(row).  Rounds of 8 rows alternate bit 3 of the row, which
-  // flips the low bit of the swizzle: two per-lane source offsets cover all rounds.
+  // ---- per-lane constants
+  // copies: lane (r4 = lane>>4, slot = lane&15) of a wave fills, in round rd, LDS row
+  // rd*kRoundRows + cp_row, slot `slot`, with the source chunk slot ^ swz(row).  Rounds of 8
+  // rows alternate bit 3 of the row, which flips the low bit of the swizzle: two per-lane
+  // source offsets cover all rounds.
+  // K operand reads: lane (n, hi) reads row 32mt + n, chunk 2ks + hi.
+  // V transpose reads: lane = 16*grp + 4e + a supplies the piece (key 16gq + 8half + 4hi + e,
+  // dims 32dt + 16(grp&1) + 4a ..) and receives keys 4hi+0..3 (+8half, +16gq) of dim 32dt + n.
   const int cp_row = 4 * wave + (lane >> 4);
   const uint32_t cp_off0 = uint32_t(cp_row) * uint32_t(row_bytes) + (((lane & 15) ^ swz(cp_row)) << 4);
   const uint32_t cp_off1 = uint32_t(cp_row) * uint32_t(row_bytes) + (((lane & 15) ^ swz(cp_row) ^ 1) << 4);
@@ -94,8 +118,12 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   uint64_t t_first = 0, t_last = 0;
   const int home = my_xcd();
   int empty_mask = 0;                    // queues this workgroup has found empty (thread 0 only)
+  int n_merge = 0;                       // rows whose last piece finished here; combined after the loop
 
   for (;;) {
+    // A workgroup that owes as many merges as it can note stops taking items; the others carry on
+    // (there are far fewer split rows in a launch than the workgroups together can note).
+    if (n_merge == kDeferredMerges) break;
     if (tid == 0) s_item = next_item(wq, home, empty_mask);
     __syncthreads();
     const int pos = __builtin_amdgcn_readfirstlane(s_item);   // uniform: keep the item's geometry in SGPRs
@@ -127,11 +155,11 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       const int j = min(max(j_raw, 0), nb - 1);
       // a sub-tile that starts past the end of a ragged last block is moved back onto the
       // last token: row offsets must stay non-negative (they are added unsigned)
-      const int key_base = min(seq_begin + j * BQ + kKeysPerTile * (t & 1), seq_end - 1);
+      const int key_base = min(seq_begin + j * BQ + KT * (t & 1), seq_end - 1);
       const int last = seq_end - 1 - key_base;
       const char* tile = head + int64_t(key_base) * row_bytes;
       const uint32_t dst = stage0 + stage * kTileBytes;
-      if (last >= kKeysPerTile - 1) {
+      if (last >= KT - 1) {
 #pragma unroll
         for (int rd = 0; rd < kRounds; ++rd) {
           const bool odd8 = ((rd * kRoundRows) >> 3) & 1;       // round starts at an odd multiple of 8 rows
@@ -180,16 +208,16 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
         for (int r = 0; r < 16; ++r) acc_o[dt][nt][r] = 0.0f;
     }
 
-    auto mask_scores = [&](f32x16 (&sc)[2][NT], int t) {          // diagonal block: keys above the query
+    auto mask_scores = [&](f32x16 (&sc)[MT][NT], int t) {          // diagonal block: keys above the query
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         // key position minus query position, up to the part that depends on the register: taken
         // through an opaque move so that the 32 comparisons are made here, on the rare diagonal
         // tile, instead of being hoisted out of the item loop into 64 scalar registers of masks
-        int d = kKeysPerTile * (t & 1) + 4 * hi - (wave * QW + 32 * nt + n);
+        int d = KT * (t & 1) + 4 * hi - (wave * QW + 32 * nt + n);
         asm volatile("" : "+v"(d));
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
           for (int r = 0; r < 16; ++r)
             if (d + (32 * mt + 8 * (r >> 2) + (r & 3)) > 0) sc[mt][nt][r] = -INFINITY;
@@ -212,8 +240,24 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       }
     };
 
-    auto read_k = [&](const char* kt, int gi) {       // operand of QK group gi = 2*ks + mt
-      return *reinterpret_cast<const bf16x8*>(kt + (k_rd0 ^ ((gi >> 1) << 5)) + (gi & 1) * 32 * kRowBytes);
+    auto read_k = [&](const char* kt, int gi) {       // operand of QK group gi = MT*ks + mt
+      const int ks = gi / MT, mt = gi % MT;
+      return *reinterpret_cast<const bf16x8*>(kt + (k_rd0 ^ (ks << 5)) + mt * 32 * kRowBytes);
+    };
+    // in-lane maximum of a tile's scores
+    auto tile_max = [&](f32x16 (&sc)[MT][NT], float (&mx)[NT]) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        if constexpr (MT == 2) {
+          mx[nt] = fmaxf(sc[0][nt][0], sc[1][nt][0]);
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx[nt] = fmaxf(mx[nt], fmaxf(sc[0][nt][r], sc[1][nt][r]));
+        } else {
+          mx[nt] = sc[0][nt][0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx[nt] = fmaxf(mx[nt], sc[0][nt][r]);
+        }
+      }
     };
     auto read_v = [&](const char* vt, int gi) {       // operand of PV group gi = 4*gq + dt
       const int gq = gi >> 2, dt = gi & 3;
@@ -223,39 +267,35 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     };
 
     // ---- prologue: S(0)
-    f32x16 sc_a[2][NT], sc_b[2][NT];
+    f32x16 sc_a[MT][NT], sc_b[MT][NT];
     wait_vmem_all();
     __syncthreads();
     {
       const char* kt = k_lds[0];
-      bf16x8 kf[16];
+      bf16x8 kf[kQK];
 #pragma unroll
-      for (int gi = 0; gi < 16; ++gi) kf[gi] = read_k(kt, gi);
+      for (int gi = 0; gi < kQK; ++gi) kf[gi] = read_k(kt, gi);
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) sc_a[mt][nt][r] = 0.0f;
 #pragma unroll
-      for (int gi = 0; gi < 16; ++gi)
+      for (int gi = 0; gi < kQK; ++gi)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          sc_a[gi & 1][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[nt][gi >> 1], sc_a[gi & 1][nt], 0, 0, 0);
+          sc_a[gi % MT][nt] =
+              __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[nt][gi / MT], sc_a[gi % MT][nt], 0, 0, 0);
       if (j0 == i) mask_scores(sc_a, 0);
       float mx[NT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        mx[nt] = fmaxf(sc_a[0][nt][0], sc_a[1][nt][0]);
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx[nt] = fmaxf(mx[nt], fmaxf(sc_a[0][nt][r], sc_a[1][nt][r]));
-      }
+      tile_max(sc_a, mx);
       settle_max(mx);
     }
 
     // One step: tile t's softmax and PV from sc_cur, tile t+1's scores into sc_nxt.
     // jv / jk: selected blocks of tiles t+1 and t+2.
-    auto step = [&](auto has_next_c, f32x16 (&sc_cur)[2][NT], f32x16 (&sc_nxt)[2][NT], int t, int jv, int jk) {
+    auto step = [&](auto has_next_c, f32x16 (&sc_cur)[MT][NT], f32x16 (&sc_nxt)[MT][NT], int t, int jv, int jk) {
       constexpr bool kHasNext = decltype(has_next_c)::value;
       // Take turns with the other workgroup of this compute unit (see kTurnShift).
       if (((uint32_t(wall_clock64()) >> kTurnShift) & 1) ^ second_wg) __builtin_amdgcn_s_setprio(1);
@@ -271,22 +311,23 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) m_use[nt] = m_ref[nt] == -INFINITY ? 0.0f : m_ref[nt];
 
-      bf16x8 kf[16], vf[16];
-      uint32_t pk[NT][2][8];
+      bf16x8 kf[kQK], vf[kPV];
+      uint32_t pk[NT][MT][8];
       float rs0[NT], rs1[NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) rs0[nt] = rs1[nt] = 0.0f;
       if (kHasNext) {
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sc_nxt[mt][nt][r] = 0.0f;
       }
 
-      // ---- S(t+1): sixteen MFMAs back to back (the operands of the second contraction are
+      // ---- S(t+1): its MFMAs back to back (the operands of the second contraction are
       // fetched behind the last K operands)
+      static_assert(kLook <= kQK && kLook <= kPV, "operand lookahead longer than a contraction");
       if (kHasNext) {
 #pragma unroll
         for (int gi = 0; gi < kLook; ++gi) kf[gi] = read_k(kn, gi);
@@ -297,13 +338,13 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       __builtin_amdgcn_sched_barrier(0);
       if (kHasNext) {
 #pragma unroll
-        for (int gi = 0; gi < 16; ++gi) {
-          if (gi + kLook < 16) kf[gi + kLook] = read_k(kn, gi + kLook);
-          else vf[gi + kLook - 16] = read_v(vc, gi + kLook - 16);
+        for (int gi = 0; gi < kQK; ++gi) {
+          if (gi + kLook < kQK) kf[gi + kLook] = read_k(kn, gi + kLook);
+          else vf[gi + kLook - kQK] = read_v(vc, gi + kLook - kQK);
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
-            sc_nxt[gi & 1][nt] =
-                __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[nt][gi >> 1], sc_nxt[gi & 1][nt], 0, 0, 0);
+            sc_nxt[gi % MT][nt] =
+                __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[gi], qf[nt][gi / MT], sc_nxt[gi % MT][nt], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
         if (jv == i) mask_scores(sc_nxt, t + 1);
@@ -319,7 +360,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
           rs0[nt] = rs1[nt] = 0.0f;
         }
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
+        for (int u = 0; u < 8 * MT; ++u) {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
             const int mt = u >> 3, r = 2 * (u & 7);
@@ -340,15 +381,10 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       {
         bool big = false;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) big = big || !(rs0[nt] + rs1[nt] <= kRowSumLimit);
+        for (int nt = 0; nt < NT; ++nt) big = big || !(rs0[nt] + rs1[nt] <= kSumLimit);
         if (__any(big)) {
           float mx[NT];
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt) {
-            mx[nt] = fmaxf(sc_cur[0][nt][0], sc_cur[1][nt][0]);
-#pragma unroll
-            for (int r = 1; r < 16; ++r) mx[nt] = fmaxf(mx[nt], fmaxf(sc_cur[0][nt][r], sc_cur[1][nt][r]));
-          }
+          tile_max(sc_cur, mx);
           settle_max(mx);
           probabilities();
         }
@@ -357,10 +393,10 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       for (int nt = 0; nt < NT; ++nt) l_run[nt] += rs0[nt] + rs1[nt];
       __builtin_amdgcn_sched_barrier(0);
 
-      // ---- O^T += V(t)^T P(t)^T: sixteen MFMAs back to back
+      // ---- O^T += V(t)^T P(t)^T: its MFMAs back to back
 #pragma unroll
-      for (int gi = 0; gi < 16; ++gi) {
-        if (gi + kLook < 16) vf[gi + kLook] = read_v(vc, gi + kLook);
+      for (int gi = 0; gi < kPV; ++gi) {
+        if (gi + kLook < kPV) vf[gi + kLook] = read_v(vc, gi + kLook);
         const int gq = gi >> 2, dt = gi & 3;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -422,14 +458,26 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
       }
     }
     if (slot >= 0) {
-      // a piece: count it; the row's last piece to finish combines all of them into the output
-      const int q0 = seq_begin + i * BQ;
-      finish_piece<BQ, 256 / NT>(sb, item->pieces, item->first_slot, item->split_index,
-                                 out + int64_t(q0) * st.q_t + int64_t(h) * st.q_h, st.q_t,
-                                 lse != nullptr ? lse + int64_t(h) * total_tokens + q0 : nullptr,
-                                 min(BQ, seq_end - q0), &s_flag, reinterpret_cast<float*>(&k_lds[0][0]),
-                                 reinterpret_cast<float*>(&v_lds[0][0]));
+      // a piece: count it; if it completes its row, note the row for the merge after the loop
+      if (count_piece(sb, item->pieces, item->split_index, &s_flag)) {
+        if (tid == 0) s_merge[n_merge] = pos;
+        n_merge += 1;
+      }
     }
+    t_last = wall_clock64();
+  }
+
+  // ---- rows whose pieces are all done and whose last piece this workgroup computed
+  for (int x = 0; x < n_merge; ++x) {
+    __syncthreads();                                   // s_merge as thread 0 left it
+    const ItemRec* item = wq.items + s_merge[x];
+    int s, h, i, nb;
+    decode_row(meta, item->row, s, h, i, nb);
+    const int q0 = meta.tok_begin[s] + i * BQ;
+    merge_row<BQ, 2 * BQ>(sb, item->pieces, item->first_slot, out + int64_t(q0) * st.q_t + int64_t(h) * st.q_h,
+                          st.q_t, lse != nullptr ? lse + int64_t(h) * total_tokens + q0 : nullptr,
+                          min(BQ, meta.tok_begin[s + 1] - q0), reinterpret_cast<float*>(&k_lds[0][0]),
+                          reinterpret_cast<float*>(&v_lds[0][0]));
     t_last = wall_clock64();
   }
 
@@ -445,21 +493,26 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
   }
 }
 
-#ifndef SHPLB_PIPE_NT
-#define SHPLB_PIPE_NT 1
-#endif
+template <int BQ>
+void launch_one(const Geometry& g, const void* q, const void* k, const void* v, const int64_t* sel_ptr,
+                const int32_t* sel_idx, void* out, float* lse, shplb_wg_stats* stats, WorkQueues wq,
+                SplitBuffers sb, int32_t n_wg, hipStream_t stream) {
+  const float scale_log2 = g.scale * 1.4426950408889634f;
+  hipLaunchKernelGGL((attn_pipe_kernel<BQ>), dim3(n_wg), dim3(2 * BQ), 0, stream, g.meta, g.st,
+                     static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                     static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
+                     stats, wq, sb, g.total_tokens, scale_log2);
+}
 
 }  // namespace
 
-void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
-                              const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                              shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg,
-                              hipStream_t stream) {
-  const float scale_log2 = g.scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((attn_pipe_kernel<SHPLB_PIPE_NT>), dim3(n_wg), dim3(256 / SHPLB_PIPE_NT), 0, stream,
-                     g.meta, g.st, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
-                     static_cast<const uint16_t*>(v), sel_ptr, sel_idx, static_cast<uint16_t*>(out), lse,
-                     stats, wq, sb, g.total_tokens, scale_log2);
+int32_t launch_attention(const Geometry& g, const void* q, const void* k, const void* v,
+                         const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
+                         shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg, hipStream_t stream) {
+  if (g.meta.block == 128) launch_one<128>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, wq, sb, n_wg, stream);
+  else launch_one<64>(g, q, k, v, sel_ptr, sel_idx, out, lse, stats, wq, sb, n_wg, stream);
+  if (hipGetLastError() != hipSuccess) return SHPLB_E_HIP;
+  return SHPLB_OK;
 }
 
 }  // namespace shplb

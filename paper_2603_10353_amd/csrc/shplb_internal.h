@@ -30,7 +30,7 @@ struct SeqMeta {
   int32_t blk_begin[SHPLB_MAX_SEQ + 1];   // cumulative block counts
   int64_t score_off[SHPLB_MAX_SEQ + 1];   // float offset of each sequence's score cube
   int32_t kv_map;                         // 1: kv_of[] holds the KV head of every query head
-  uint8_t kv_of[SHPLB_MAX_MAPPED_HEADS];
+  uint32_t kv_of[SHPLB_MAX_MAPPED_HEADS / 4];   // one byte per query head, four to a word
 };
 
 struct Strides {
@@ -70,7 +70,9 @@ int32_t make_geometry(const shplb_problem* p, Geometry* g);
 // split_slots: partial-result slots for rows split along the keys (0: rows stay whole)
 // with_pooled = false leaves out the pooled planes (the attention step alone does not use them)
 WorkspaceLayout make_layout(const Geometry& g, int32_t split_slots = 0, bool with_pooled = true);
-int32_t persistent_workgroups();   // for the current device; <0 on HIP error
+// Persistent workgroups of an attention launch on the current device: as many as fit at two waves
+// per SIMD (two per compute unit with 128-token blocks, four with 64); <0 on HIP error.
+int32_t persistent_workgroups(int block = 128);
 
 // Kernel launchers (each returns a SHPLB status).
 int32_t launch_pool_scores(const Geometry& g, const void* q, const void* k, float* scores,
@@ -144,15 +146,9 @@ int32_t launch_attention(const Geometry& g, const void* q, const void* k, const 
                          const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
                          shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg, hipStream_t stream);
 
-// Pipelined variant for 128-token blocks (attn_pipe_kernel.hip).
-void launch_attention_pipe128(const Geometry& g, const void* q, const void* k, const void* v,
-                              const int64_t* sel_ptr, const int32_t* sel_idx, void* out, float* lse,
-                              shplb_wg_stats* stats, WorkQueues wq, SplitBuffers sb, int32_t n_wg,
-                              hipStream_t stream);
-
 // KV head that query head h reads: the caller's map, or equal groups of consecutive heads.
 __device__ __forceinline__ int kv_head_of(const SeqMeta& m, int h) {
-  return m.kv_map ? int(m.kv_of[h]) : h / (m.n_q_heads / m.n_kv_heads);
+  return m.kv_map ? int(m.kv_of[h >> 2] >> (8 * (h & 3)) & 0xff) : h / (m.n_q_heads / m.n_kv_heads);
 }
 
 // Row -> (sequence, head, query block).  Rows of one sequence are contiguous.

@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--workload", required=True, help="bench.py --workload value the runs were made with")
     ap.add_argument("--warmup", type=int, default=2, help="--warmup of the kernel-trace run")
     ap.add_argument("--dir", default="gpurun_out", help="where the rocprofv3 output directories are")
-    ap.add_argument("--kernel", default="attn_pipe_kernel<1>", help="dominant kernel (traffic line, SQ counters)")
+    ap.add_argument("--kernel", default="attn_pipe_kernel<128>", help="dominant kernel (traffic line, SQ counters)")
     ap.add_argument("--out", required=True)
     args = ap.parse_args()
     wl, d = args.workload, args.dir
