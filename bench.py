@@ -196,7 +196,7 @@ class Pass:
         imb_time = float(busy[active].max() / busy[active].mean() - 1.0) if active.any() else None
         cost = st["cost_blocks"].astype(np.float64)
         span = float(st["t_last"][active].max() - st["t_first"][active].min())
-        kernel = "attn_pipe_kernel" if wl.block == 128 else "attn_kernel"
+        kernel = "attn_pipe_kernel"
         attn_tflops = flops / (attn_ms * 1e-3) / 1e12
         return {
             "ms_per_step": ms_per_step, "value": flops / (ms_per_step * 1e-3) / 1e12,

@@ -86,3 +86,14 @@ def test_profile_feeds_budget_shifting_and_rates_the_selection():
     # on this synthetic layer it keeps 0.71 of the attention weight on average where the ideal choice
     # of the same size keeps 0.81; single heads fall as low as 0.55 of their ideal.
     assert kept.mean() >= 0.8 * best.mean() and np.all(kept >= 0.4 * best)
+
+
+def test_block_mass_32k_layer_sampled_rows():
+    # The 32K layer at full size: the profile of 24 seeded rows plus the last row of four heads (256 key
+    # blocks each) against the oracle; every row of the whole profile must sum to one.
+    wl = make_workload(1)
+    nb, hq = wl.n_blocks[0], wl.n_q_heads
+    rng = np.random.default_rng(11)
+    rows = set(rng.choice(nb * hq, size=24, replace=False).tolist())
+    rows |= {h * nb + nb - 1 for h in (0, 9, 18, 31)}
+    _profile(wl, rows=sorted(rows))
