@@ -85,7 +85,8 @@ __global__ __launch_bounds__(2 * BQ) void mass_kernel(SeqMeta meta, Strides st, 
   const int n_valid = min(BQ, seq_end - seq_begin - i * BQ);
   float* out_row = mass + meta.score_off[s] + (int64_t(h) * nb + i) * nb;
 
-  // scores of tile `it` from stage `buf`, in the log2 domain, keys above the query at -inf
+  // raw scores (q . k, unscaled) of tile `it` from stage `buf`; on the diagonal block the keys above the
+  // query are set to -inf (only there: the test is uniform, so other tiles pay nothing for it)
   auto scores_of = [&](int it, int buf, f32x16 (&sc)[2]) {
     const char* kt = k_lds[buf];
     bf16x8 kf[2][8];
@@ -104,17 +105,21 @@ __global__ __launch_bounds__(2 * BQ) void mass_kernel(SeqMeta meta, Strides st, 
       for (int mt = 0; mt < 2; ++mt)
         sc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][ks], qf[ks], sc[mt], 0, 0, 0);
     const int j = it / SUB, sub = it - j * SUB;
-    const int q_in = wave * 32 + n;
+    if (j == i) {
+      int d = kKeysPerTile * sub + 4 * hi - (wave * 32 + n);      // key position minus query position, per register below
+      asm volatile("" : "+v"(d));                                  // keep the 32 comparisons here, not hoisted as masks
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key_in = kKeysPerTile * sub + 32 * mt + 8 * (r >> 2) + 4 * hi + (r & 3);
-        sc[mt][r] = (j == i && key_in > q_in) ? -INFINITY : sc[mt][r] * scale_log2;
-      }
+        for (int r = 0; r < 16; ++r)
+          if (d + (32 * mt + 8 * (r >> 2) + (r & 3)) > 0) sc[mt][r] = -INFINITY;
+    }
   };
 
-  // ---- sweep A: log2 of the softmax denominator of the lane's query
+  // ---- sweep A: log2 of the softmax denominator of the lane's query.  The sum runs against a reference
+  // exponent that is only raised when a tile's maximum exceeds it by more than 2^8 (then the sum so far
+  // is rescaled): exact in real arithmetic, and most tiles cost one fused multiply-add, one exponential
+  // and one addition per score, plus the maximum.
   float m_run = -INFINITY, l_run = 0.0f;
   int step = 0;                                     // tiles handled so far over both sweeps: stage = step & 1
   for (int it = 0; it < n_tiles; ++it, ++step) {
@@ -126,15 +131,19 @@ __global__ __launch_bounds__(2 * BQ) void mass_kernel(SeqMeta meta, Strides st, 
     float mx = fmaxf(sc[0][0], sc[1][0]);
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sc[0][r], sc[1][r]));
-    const float m_new = fmaxf(m_run, mx);
-    if (m_new != -INFINITY) {                       // all keys of the lane masked so far: nothing to add
-      float sum = 0.0f;
+    mx *= scale_log2;
+    if (mx > m_run + kRescaleSlack) {               // per lane: a lane's reference follows its own keys
+      l_run *= m_run == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(m_run - mx);
+      m_run = mx;
+    }
+    if (m_run != -INFINITY) {                       // all keys of the lane masked so far: nothing to add
+      float sum0 = 0.0f, sum1 = 0.0f;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(sc[mt][r] - m_new);
-      l_run = l_run * (m_run == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(m_run - m_new)) + sum;
-      m_run = m_new;
+      for (int r = 0; r < 16; ++r) {
+        sum0 += __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][r], scale_log2, -m_run));
+        sum1 += __builtin_amdgcn_exp2f(__builtin_fmaf(sc[1][r], scale_log2, -m_run));
+      }
+      l_run += sum0 + sum1;
     }
   }
   float lse2;
@@ -164,12 +173,13 @@ __global__ __launch_bounds__(2 * BQ) void mass_kernel(SeqMeta meta, Strides st, 
     }
     f32x16 sc[2];
     scores_of(it, step & 1, sc);
-    float sum = 0.0f;
+    float sum0 = 0.0f, sum1 = 0.0f;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(sc[mt][r] - lse2);
-    acc += live ? sum : 0.0f;
+    for (int r = 0; r < 16; ++r) {
+      sum0 += __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][r], scale_log2, -lse2));
+      sum1 += __builtin_amdgcn_exp2f(__builtin_fmaf(sc[1][r], scale_log2, -lse2));
+    }
+    acc += live ? sum0 + sum1 : 0.0f;
     if (sub == SUB - 1) {
 #pragma unroll
       for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d);
