@@ -55,3 +55,32 @@ def test_static_scratch_refuses_what_does_not_fit():
     with pytest.raises(S.ShplbError) as e:
         S.shplb_sparse_attn_prefill_static(wl_shape, one, one, one, one, one, one, None, None, None)
     assert e.value.status == -4
+
+
+def test_static_scratch_entry_point_in_a_hip_graph():
+    # What the entry point is for: captured into a HIP graph (after one call outside the capture, which
+    # looks up the array's address) and replayed with eager work in between; every replay must
+    # reproduce the workspace entry point's result bit for bit.
+    from harness import GpuRun
+    wl = make_workload(1, seqlens=[128 * 29 + 17])
+    run = GpuRun(wl).run_all()
+    ref_out, ref_lse = run.out.clone(), run.lse.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        S.shplb_sparse_attn_prefill_static(run.p, run.q, run.k, run.v, run.sel_ptr, run.sel_idx, run.out, run.lse,
+                                           None, side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            S.shplb_sparse_attn_prefill_static(run.p, run.q, run.k, run.v, run.sel_ptr, run.sel_idx, run.out,
+                                               run.lse, None, side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        run.out.zero_(); run.lse.zero_()
+        run.ws.random_(0, 255)                       # eager work between replays; the workspace is not used
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(run.out.view(torch.int16), ref_out.view(torch.int16)), replay
+        assert torch.equal(run.lse, ref_lse), replay
