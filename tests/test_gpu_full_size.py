@@ -127,6 +127,18 @@ def test_config4_varlen_batch_full():
     _constant_value_pass(run)
 
 
+def test_block64_32k_layer():
+    # The 32K layer with 64-token blocks and the same budgets in tokens (twice as many blocks): 16 384 rows
+    # of up to 256 blocks through the 64-token instance of the pipelined kernel (32-key tiles, four
+    # workgroups per compute unit).
+    from workloads import layer_budgets, make_custom
+    budgets = 2 * layer_budgets(1, [32768])["budgets"][0]
+    wl = make_custom([32768], 32, 8, 64, [int(x) for x in budgets], seed=5, c_range=(0.25, 6.0), name="layer32k_b64")
+    run, imb = _run_case(wl, 40, seed=9)
+    assert imb < 0.05
+    _constant_value_pass(run)
+
+
 def test_three_sequences_above_the_single_workgroup_ordering():
     # 17 024 rows (> 16 384, where the single-workgroup ordering ends) from three ragged sequences
     # of a 64/16-head layer: the five-launch ordering with multi-sequence decoding at a size where
