@@ -86,6 +86,13 @@ __global__ __launch_bounds__(kPoolThreads) __attribute__((amdgpu_waves_per_eu(2,
     if (hh < n_heads) {
       float v0 = (((part[0][x] + part[1][x]) + part[2][x]) + part[3][x]) / float(cnt);
       float v1 = (((part[0][x + 1] + part[1][x + 1]) + part[2][x + 1]) + part[3][x + 1]) / float(cnt);
+      if (is_q) {
+        // query means stay fp32: the scoring kernel loads each row into registers anyway and splits it
+        // there (two thirds of the bytes of three planes, on a buffer that is written once and read 2.5 times)
+        float* qm = reinterpret_cast<float*>(q_planes) + (int64_t(hh) * total_blocks + gblk) * kHeadDim + dd;
+        *reinterpret_cast<float2*>(qm) = float2{v0, v1};
+        return;
+      }
       uint16_t* at = dst + (int64_t(hh) * total_blocks + gblk) * kHeadDim + dd;
 #pragma unroll
       for (int pl = 0; pl < 3; ++pl) {
@@ -148,7 +155,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const int i_first = ti + 32 * wave;               // this wave's rows
   const int i_last = min(ti + kScoreTile, nb) - 1;  // last row of the workgroup
   const int n_jt = (min(tj + chunk, i_last + 1) - tj + kScoreJ - 1) / kScoreJ;   // 32-row K tiles with some j <= i
-  const int64_t q_plane = int64_t(meta.n_q_heads) * total_blocks * kHeadDim;   // elements per plane
   const int64_t k_plane = int64_t(meta.n_kv_heads) * total_blocks * kHeadDim;
   const char* k_rows = reinterpret_cast<const char*>(k_planes + (int64_t(g) * total_blocks + meta.blk_begin[s]) * kHeadDim);
 
@@ -169,15 +175,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   };
   issue_tile(0, 0);
 
-  // Q planes of row i_first + n: B operands, lane (n, hi) holds dims 16ks + 8hi .. +7
+  // Q planes of row i_first + n: B operands, lane (n, hi) holds dims 16ks + 8hi .. +7.  The means arrive
+  // as fp32 and are split here into the three bf16 planes (v1 = bf16(v), v2 = bf16(v - v1),
+  // v3 = bf16(v - v1 - v2); the differences are exact), as the pooling kernel does for the keys.
   bf16x8 qf[kPlanes][8];
   {
     const int i = min(i_first + n, nb - 1);
-    const uint16_t* src = q_planes + (int64_t(h) * total_blocks + meta.blk_begin[s] + i) * kHeadDim + 8 * hi;
+    const float* src = reinterpret_cast<const float*>(q_planes) +
+                       (int64_t(h) * total_blocks + meta.blk_begin[s] + i) * kHeadDim + 8 * hi;
+    f32x4 raw[8][2];
 #pragma unroll
-    for (int pl = 0; pl < kPlanes; ++pl)
+    for (int ks = 0; ks < 8; ++ks) {
+      raw[ks][0] = *reinterpret_cast<const f32x4*>(src + 16 * ks);
+      raw[ks][1] = *reinterpret_cast<const f32x4*>(src + 16 * ks + 4);
+    }
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) qf[pl][ks] = *reinterpret_cast<const bf16x8*>(src + pl * q_plane + 16 * ks);
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        float v = raw[ks][c >> 2][c & 3];
+#pragma unroll
+        for (int pl = 0; pl < kPlanes; ++pl) {
+          const __bf16 b = (__bf16)v;
+          qf[pl][ks][c] = b;
+          v -= float(b);
+        }
+      }
   }
   typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
   const uint32_t k_rd0 = lds_offset_of(&k_lds[0][0]) + uint32_t(n * kRowBytes + ((hi ^ swz(n)) << 4));
