@@ -43,6 +43,11 @@ What the paper fixes and what it leaves open
     heaviest blocks of a row, averaged over all queries of the head (rows with fewer
     than b visible blocks recover everything).  The paper profiles tokens (k = 4096);
     blocks are what the path's budgets count.
+  * The same ratio at the paper's own granularity (token_recovery): for every query
+    token the sum of its k largest attention weights, Eq. 1 weights under the causal
+    mask; a query that sees no more than k keys recovers 1; a head's figure is the mean
+    over its queries (the paper plots one number per head and does not say how the
+    queries are combined).
 
 Pins (tests/test_oracle_*.py): dense special case vs a textbook attention routine,
 row sums, constant-V, sink+diagonal special case, selection-order invariance,
@@ -51,7 +56,9 @@ instance, exhaustive optimum on tiny partitions, cost closed form; budget shifti
 hand-worked instance, identical curves, exhaustive max-min optimum for two heads,
 invariants on random monotone curves; block mass: rows sum to one, closed form for
 constant keys, block sums of a textbook softmax; recovery curves: closed forms for
-uniform and one-hot rows, monotone and concave in the budget.
+uniform and one-hot rows, monotone and concave in the budget; token recovery: closed form
+for constant keys, top-k sums of a textbook softmax, best subset by exhaustive search,
+k = 1 is the largest weight, whole blocks of equal keys against the block profile.
 Parity unpinned: how well pooled-score selection tracks true attention mass (needs
 the paper's models and data); only self-consistency is checked.
 """
@@ -395,3 +402,36 @@ def selection_recovery(mass: List[np.ndarray], cu_seqlens: Sequence[int], block:
                 r = row_index(cu, block, n_heads, s, h, i)
                 got[h] += n_valid * mass[s][h, i, sel_idx[sel_ptr[r]:sel_ptr[r + 1]]].sum()
     return got / n_queries
+
+
+def token_recovery(q_bits: np.ndarray, k_bits: np.ndarray, cu_seqlens: Sequence[int],
+                   budgets: Sequence[int], softmax_scale: Optional[float] = None,
+                   tokens: Optional[Sequence[int]] = None) -> np.ndarray:
+    """Recovery ratio of Section 2.4 at token granularity: out[b, h, t] = sum of the budgets[b]
+    largest attention weights (Eq. 1, causal) of query token t of head h; a query that sees at
+    most budgets[b] keys recovers 1.  fp64 [len(budgets), Hq, T]; NaN at tokens not asked for
+    (`tokens`: global token indices; None = all)."""
+    q = decode_bf16(q_bits)
+    k = decode_bf16(k_bits)
+    n_q_heads, n_kv_heads, d = q.shape[1], k.shape[1], q.shape[2]
+    group = n_q_heads // n_kv_heads
+    scale = 1.0 / math.sqrt(d) if softmax_scale is None else float(softmax_scale)
+    cu = [int(x) for x in cu_seqlens]
+    out = np.full((len(budgets), n_q_heads, cu[-1]), np.nan)
+    want = range(cu[-1]) if tokens is None else sorted(set(int(t) for t in tokens))
+    for t in want:
+        s = max(x for x in range(len(cu) - 1) if cu[x] <= t)
+        for h in range(n_q_heads):
+            logits = k[cu[s]:t + 1, h // group, :] @ q[t, h, :] * scale          # the keys the query sees
+            w = np.exp(logits - logits.max())
+            w /= w.sum()
+            largest_first = np.sort(w)[::-1]
+            for b, budget in enumerate(budgets):
+                out[b, h, t] = 1.0 if budget >= len(w) else largest_first[:int(budget)].sum()
+    return out
+
+
+def token_recovery_heads(recovery: np.ndarray) -> np.ndarray:
+    """Per-head figure: mean over the queries (all sequences) of token_recovery's output,
+    [Hq, len(budgets)]; tokens not asked for (NaN) are left out."""
+    return np.nanmean(recovery, axis=2).T
