@@ -12,6 +12,8 @@
  *   shplb_shift_budgets         max-min budget shifting: the producer of the budgets (host)
  *   shplb_block_mass            offline recovery profile: attention weight per block pair
  *   shplb_recovery_curves       recovery ratio per head and budget from that profile (host)
+ *   shplb_token_recovery        offline recovery ratio at token granularity, per query
+ *   shplb_token_recovery_heads  its mean per head (host)
  *
  * Conventions
  *   - Every function returns an int32 status: 0 = OK, negative = error (see
@@ -62,6 +64,7 @@ extern "C" {
 #define SHPLB_MAX_BLOCKS   4096    /* blocks per sequence */
 #define SHPLB_MAX_SEQ_HEADS 65535  /* n_seq * n_q_heads per call */
 #define SHPLB_MAX_MAPPED_HEADS 256  /* n_q_heads and n_kv_heads with an explicit kv_head_of */
+#define SHPLB_MAX_TOKEN_BUDGETS 8  /* budgets per shplb_token_recovery call */
 
 typedef struct {
   int32_t n_seq;                 /* 1..SHPLB_MAX_SEQ */
@@ -230,6 +233,32 @@ SHPLB_API int32_t shplb_block_mass(const shplb_problem* p, const void* q, const 
  * Errors: SHPLB_E_NULL, SHPLB_E_SHAPE (also a wrong n_levels). */
 SHPLB_API int32_t shplb_recovery_curves(const shplb_problem* p, const float* mass, int32_t n_levels,
                               double* curves_out);
+
+/* Recovery ratio as the paper profiles it (Section 2.4: the cumulative attention
+ * weight of a query's top-k tokens, k = 4096 there): under full causal attention
+ * (Eq. 1), recovery_out[b][h][t] = the sum of the budgets[b] largest attention
+ * weights of query token t of head h; a query that sees at most budgets[b] keys
+ * recovers exactly 1.  Exact selection (the k-th largest weight of every query is
+ * found by a bitwise search over dense sweeps, ties at the k-th place counted at
+ * that weight), fp32 softmax statistics, bf16 MFMA products; a dense pass of some
+ * 20 to 33 sweeps over the causal triangle: an offline tool.
+ *   q, k: device bf16.  budgets: host [n_budgets], tokens, each >= 1;
+ *   n_budgets: 1..SHPLB_MAX_TOKEN_BUDGETS.
+ *   recovery_out: device fp32 [n_budgets][n_q_heads][T], T = cu_seqlens[n_seq].
+ * Errors: SHPLB_E_NULL, SHPLB_E_SHAPE (alignment), SHPLB_E_BUDGET (a budget < 1),
+ * SHPLB_E_UNSUPPORTED (n_budgets out of range). */
+SHPLB_API int32_t shplb_token_recovery(const shplb_problem* p, const void* q, const void* k,
+                             const int32_t* budgets /*host*/, int32_t n_budgets,
+                             float* recovery_out, void* stream);
+
+/* One figure per head and budget from shplb_token_recovery's output, as the paper
+ * plots it (Section 2.4 does not say how a head's queries are combined; here: the
+ * mean over all queries of the head, all sequences).  All pointers are host memory.
+ *   recovery: host fp32 [n_budgets][n_q_heads][T] (copied from the device by the
+ *   caller).  heads_out: [n_q_heads][n_budgets] doubles.
+ * Errors: SHPLB_E_NULL, SHPLB_E_UNSUPPORTED (n_budgets out of range). */
+SHPLB_API int32_t shplb_token_recovery_heads(const shplb_problem* p, const float* recovery,
+                                   int32_t n_budgets, double* heads_out);
 
 /* ---- host step ------------------------------------------------------------ */
 

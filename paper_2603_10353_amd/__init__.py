@@ -28,5 +28,7 @@ from .binding import (  # noqa: F401
     shplb_sparse_attn_prefill_static,
     shplb_split_workspace_bytes,
     shplb_strerror,
+    shplb_token_recovery,
+    shplb_token_recovery_heads,
     shplb_workspace_bytes,
 )

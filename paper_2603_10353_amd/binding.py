@@ -15,7 +15,8 @@ EXPORTS = [
     "shplb_sched_num_workgroups", "shplb_block_scores", "shplb_select_topk_per_head",
     "shplb_sparse_attn_prefill", "shplb_sparse_attn_prefill_static", "shplb_split_workspace_bytes", "shplb_sparse_attn_prefill_split",
     "shplb_balance_heads", "shplb_shift_budgets", "shplb_block_mass",
-    "shplb_recovery_curves", "shplb_probe_mfma_rate", "shplb_strerror",
+    "shplb_recovery_curves", "shplb_token_recovery", "shplb_token_recovery_heads", "shplb_probe_mfma_rate",
+    "shplb_strerror",
 ]
 
 
@@ -91,6 +92,8 @@ def load_library():
     lib.shplb_probe_mfma_rate.argtypes = [i32, i32, i32, vp, vp]
     lib.shplb_block_mass.argtypes = [pp, vp, vp, vp, vp]
     lib.shplb_recovery_curves.argtypes = [pp, C.POINTER(C.c_float), i32, C.POINTER(C.c_double)]
+    lib.shplb_token_recovery.argtypes = [pp, vp, vp, C.POINTER(C.c_int32), i32, vp, vp]
+    lib.shplb_token_recovery_heads.argtypes = [pp, C.POINTER(C.c_float), i32, C.POINTER(C.c_double)]
     lib.shplb_shift_budgets.argtypes = [C.POINTER(C.c_double), i32, i32, i64, i32, i32, C.POINTER(i32),
                                         C.POINTER(i64)]
     for name in EXPORTS[:-1]:
@@ -290,6 +293,26 @@ def shplb_recovery_curves(p: Problem, mass_host) -> np.ndarray:
                                                 curves.ctypes.data_as(C.POINTER(C.c_double))),
            "shplb_recovery_curves")
     return curves
+
+
+def shplb_token_recovery(p: Problem, q, k, budgets, recovery_out, stream=None) -> None:
+    """budgets: host int32 [n_budgets] (tokens); recovery_out: device float32 [n_budgets, n_q_heads, T]."""
+    b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32)).reshape(-1)
+    _check(load_library().shplb_token_recovery(p.ref(), _dev(q), _dev(k), b.ctypes.data_as(C.POINTER(C.c_int32)),
+                                               int(b.size), _dev(recovery_out), _stream(stream)),
+           "shplb_token_recovery")
+
+
+def shplb_token_recovery_heads(p: Problem, recovery_host) -> np.ndarray:
+    """recovery_host: float32 host array [n_budgets, n_q_heads, T].  Returns float64 [n_q_heads, n_budgets]."""
+    r = np.ascontiguousarray(np.asarray(recovery_host, dtype=np.float32))
+    if r.ndim != 3 or r.shape[1] != p.c.n_q_heads or r.shape[2] != int(p.cu[-1]):
+        raise ValueError("recovery must be [n_budgets, n_q_heads, T]")
+    heads = np.zeros((p.c.n_q_heads, r.shape[0]), np.float64)
+    _check(load_library().shplb_token_recovery_heads(p.ref(), r.ctypes.data_as(C.POINTER(C.c_float)), int(r.shape[0]),
+                                                     heads.ctypes.data_as(C.POINTER(C.c_double))),
+           "shplb_token_recovery_heads")
+    return heads
 
 
 def shplb_probe_mfma_rate(random_operands: bool, iters: int, n_workgroups: int, scratch, stream=None) -> None:

@@ -313,6 +313,37 @@ int32_t shplb_block_mass(const shplb_problem* p, const void* q, const void* k, f
   return launch_block_mass(g, q, k, mass_out, static_cast<hipStream_t>(stream));
 }
 
+// Offline recovery ratio of Section 2.4 at token granularity: the top-k weights of every query.
+int32_t shplb_token_recovery(const shplb_problem* p, const void* q, const void* k, const int32_t* budgets,
+                             int32_t n_budgets, float* recovery_out, void* stream) {
+  if (!q || !k || !recovery_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 15) return SHPLB_E_SHAPE;
+  if (n_budgets < 1 || n_budgets > SHPLB_MAX_TOKEN_BUDGETS) return SHPLB_E_UNSUPPORTED;
+  if (!budgets) return SHPLB_E_NULL;
+  for (int b = 0; b < n_budgets; ++b)
+    if (budgets[b] < 1) return SHPLB_E_BUDGET;
+  return launch_token_recovery(g, q, k, budgets, n_budgets, recovery_out, static_cast<hipStream_t>(stream));
+}
+
+int32_t shplb_token_recovery_heads(const shplb_problem* p, const float* recovery, int32_t n_budgets,
+                                   double* heads_out) {
+  if (!recovery || !heads_out) return SHPLB_E_NULL;
+  Geometry g;
+  if (int32_t st = make_geometry(p, &g)) return st;
+  if (n_budgets < 1 || n_budgets > SHPLB_MAX_TOKEN_BUDGETS) return SHPLB_E_UNSUPPORTED;
+  const int64_t tokens = g.total_tokens;
+  for (int h = 0; h < g.meta.n_q_heads; ++h)
+    for (int b = 0; b < n_budgets; ++b) {
+      const float* src = recovery + (int64_t(b) * g.meta.n_q_heads + h) * tokens;
+      double sum = 0.0;
+      for (int64_t t = 0; t < tokens; ++t) sum += src[t];
+      heads_out[int64_t(h) * n_budgets + b] = sum / double(tokens);
+    }
+  return SHPLB_OK;
+}
+
 int32_t shplb_recovery_curves(const shplb_problem* p, const float* mass, int32_t n_levels, double* curves_out) {
   if (!mass || !curves_out) return SHPLB_E_NULL;
   Geometry g;

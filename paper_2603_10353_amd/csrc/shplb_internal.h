@@ -83,6 +83,8 @@ int32_t launch_order(const Geometry& g, const int64_t* sel_ptr, const WorkspaceL
                      char* workspace, int32_t n_wg, hipStream_t stream);
 int32_t launch_mfma_rate(int random_operands, int iters, int n_workgroups, void* scratch, hipStream_t stream);
 int32_t launch_block_mass(const Geometry& g, const void* q, const void* k, float* mass, hipStream_t stream);
+int32_t launch_token_recovery(const Geometry& g, const void* q, const void* k, const int32_t* budgets,
+                              int32_t n_budgets, float* recovery, hipStream_t stream);
 // One work item of an attention launch: a row, or one piece of a row that was split along
 // its selected key blocks (positions [first, first + n_sel) of the row's selection).
 struct alignas(32) ItemRec {

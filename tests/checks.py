@@ -9,6 +9,8 @@ OUT_MAX_ABS = 2e-2     # bf16 inputs, bf16 P, fp32 accumulate
 OUT_MAX_REL = 1e-2     # max|diff| / max|oracle| per head
 MASS_RTOL = 2e-4      # block mass: fp32 exp2 of fp32 logits (|s| of a few tens) and fp32 sums of up to 16K terms
 MASS_ATOL = 1e-7
+TOKEN_RECOVERY_RTOL = 2e-4   # sums of at most k fp32 weights, each exp2 of an fp32 log-weight (|y| of a few tens)
+TOKEN_RECOVERY_ATOL = 1e-7
 LSE_ATOL = 4e-3        # l sums the bf16-rounded probabilities: relative error up to 2^-9, plus fp32 exp/log
 
 

@@ -72,6 +72,13 @@ class GpuRun:
             self.mass = torch.full_like(self.scores, float("nan"))
         S.shplb_block_mass(self.p, self.q, self.k, self.mass, torch.cuda.current_stream())
 
+    def token_recovery_step(self, budgets):
+        """Offline token-granular recovery ratio, [len(budgets), heads, tokens] on the device."""
+        shape = (len(budgets), self.wl.n_q_heads, self.q.shape[0])
+        if getattr(self, "token_recovery", None) is None or tuple(self.token_recovery.shape) != shape:
+            self.token_recovery = torch.full(shape, float("nan"), dtype=torch.float32, device="cuda:0")
+        S.shplb_token_recovery(self.p, self.q, self.k, budgets, self.token_recovery, torch.cuda.current_stream())
+
     def mass_flat_host(self):
         return self.mass.cpu().numpy()
 

@@ -205,3 +205,23 @@ def test_recovery_curves_vs_oracle_on_host():
     np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-15)
     with pytest.raises(ValueError):
         S.shplb_recovery_curves(p, flat[:-1])
+
+
+def test_token_recovery_host_side():
+    # the per-head mean is host work; the device entry point checks its arguments before any launch
+    from workloads import make_custom
+    wl = make_custom([70, 33], 4, 2, 64, [2] * 8, seed=45)
+    rec = orc.token_recovery(wl.q, wl.k, wl.cu_seqlens, [1, 5, 40]).astype(np.float32)
+    p = S.Problem(wl.cu_seqlens, 4, 2, 64)
+    got = S.shplb_token_recovery_heads(p, rec)
+    np.testing.assert_allclose(got, orc.token_recovery_heads(rec.astype(np.float64)), rtol=1e-12)
+    with pytest.raises(ValueError):
+        S.shplb_token_recovery_heads(p, rec[:, :, :-1])
+    with pytest.raises(S.ShplbError) as e:
+        S.shplb_token_recovery(p, None, None, [4], None)
+    assert e.value.status == -1
+    fake = 4096                                            # never dereferenced: rejected on the host
+    for budgets, status in (([0], -3), ([4, -1], -3), ([], -5), (list(range(1, 10)), -5)):
+        with pytest.raises(S.ShplbError) as e:
+            S.shplb_token_recovery(p, fake, fake, budgets, fake)
+        assert e.value.status == status, budgets
