@@ -228,7 +228,8 @@ def main():
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the two short MFMA-only launches that measure what the matrix pipe sustains")
     ap.add_argument("--profile-pass", action="store_true",
-                    help="also time the offline recovery profile (shplb_block_mass, a dense pass; not part of a step)")
+                    help="also time the offline recovery profiles (shplb_block_mass, shplb_token_recovery: dense passes; "
+                         "not part of a step)")
     ap.add_argument("--split-slots", type=int, default=0,
                     help="run the attention step through shplb_sparse_attn_prefill_split with this many "
                          "partial-result slots (long rows cut along the keys); 0 = whole rows")
@@ -354,6 +355,19 @@ def main():
                                   "frac_of_bf16_mfma_peak_executed": 2 * 2.0 * wl.head_dim * causal_pairs
                                   / (mass_ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
         del mass
+        # the same ratio at token granularity, at the budget Section 2.4 profiles (k = 4096 tokens)
+        rec = torch.empty((1, wl.n_q_heads, int(wl.cu_seqlens[-1])), dtype=torch.float32, device="cuda:0")
+        S.shplb_token_recovery(run.p, run.q, run.k, [4096], rec, stream)
+        torch.cuda.synchronize()
+        e0.record()
+        S.shplb_token_recovery(run.p, run.q, run.k, [4096], rec, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        heads = S.shplb_token_recovery_heads(run.p, rec.cpu().numpy())
+        result["profile_pass"]["token_recovery_k4096"] = {
+            "kernel": "token_recovery_kernel", "ms": e0.elapsed_time(e1),
+            "recovery_per_head_min_max": [float(heads.min()), float(heads.max())]}
+        del rec
 
     if not args.no_cpu_baseline:
         idx_h = run.sel_idx.cpu().numpy()
