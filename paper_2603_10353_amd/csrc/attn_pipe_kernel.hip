@@ -424,7 +424,7 @@ void attn_pipe_kernel(SeqMeta meta, Strides st, const uint16_t* __restrict__ q,
     for (int nt = 0; nt < NT; ++nt) {
       const float l_tot = pair_sum(l_run[nt]);
       if (slot >= 0) {
-        // a piece of a split row: O and l as they stand (relative to 2^m_ref), for finish_piece()
+        // a piece of a split row: O and l as they stand (relative to 2^m_ref), for merge_row()
         const int q_in = wave * QW + 32 * nt + n;
         float* part = sb.part_o + int64_t(slot) * kSlotFloatsO;
 #pragma unroll

@@ -20,7 +20,7 @@
 // longer than split_length() are cut along their selected key blocks into near-equal pieces,
 // each an item of its own (the pieces of a row sit next to each other, where the row would).
 // A piece leaves a partial result in a slot of the workspace; the piece of a row that finishes
-// last combines them (finish_piece() in attn_common.h).  Slots and counter entries are handed
+// last combines them (count_piece() and merge_row() in attn_common.h).  Slots and counter entries are handed
 // out through atomic counters, so their numbering varies between runs; what is computed does
 // not depend on it.
 #include "shplb_internal.h"

@@ -21,7 +21,7 @@ def bf16_tensor_to_f64(t: torch.Tensor) -> np.ndarray:
     return t.to(torch.float32).cpu().numpy().astype(np.float64)
 
 
-class GpuRun:
+class DevicePass:
     """Device-resident state of one pass of the path over a workload."""
 
     def __init__(self, wl, softmax_scale: float = 0.0, want_stats: bool = True, want_lse: bool = True):

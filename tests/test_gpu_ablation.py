@@ -23,7 +23,7 @@ SEQLEN, DEGREE = 65536, 4
 def test_greedy_parts_are_real_shares_and_not_slower_than_consecutive_heads():
     import paper_2603_10353_amd as S
     import balance_ablation as ab
-    from harness import GpuRun
+    from harness import DevicePass
 
     layer = make_workload(2, seqlens=[SEQLEN])
     n_heads = CONFIGS[2]["n_q_heads"]
@@ -51,7 +51,7 @@ def test_greedy_parts_are_real_shares_and_not_slower_than_consecutive_heads():
     share = ab.share_of(layer, part)
     g = layer.n_q_heads // layer.n_kv_heads
     assert share.n_kv_heads == len({h // g for h in part}) and share.n_q_heads == len(part)
-    run = GpuRun(share).run_all()
+    run = DevicePass(share).run_all()
     counts = np.diff(run.sel_ptr_host)
     rows = set(np.argsort(-counts, kind="stable")[:2].tolist())
     rows |= set(np.random.default_rng(3).choice(len(counts), size=24, replace=False).tolist())

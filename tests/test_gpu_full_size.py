@@ -17,10 +17,10 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_case(wl, n_sample, seed):
-    from harness import GpuRun
+    from harness import DevicePass
     print("case", wl.name, "seqlens", np.diff(wl.cu_seqlens).tolist(), "heads", wl.n_q_heads, wl.n_kv_heads,
           "budgets", wl.budgets.tolist()[:8], "...", flush=True)
-    run = GpuRun(wl).run_all()
+    run = DevicePass(wl).run_all()
     sc_o = orc.block_scores(wl.q, wl.k, wl.cu_seqlens, wl.block)
     sc_g = run.scores_host()
     for s in range(wl.n_seq):

@@ -12,8 +12,8 @@ pytestmark = pytest.mark.gpu
 
 
 def _gpu():
-    from harness import GpuRun
-    return GpuRun
+    from harness import DevicePass
+    return DevicePass
 
 
 def full_parity(wl, softmax_scale=0.0, rows=None):

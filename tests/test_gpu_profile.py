@@ -14,10 +14,10 @@ pytestmark = pytest.mark.gpu
 
 
 def _profile(wl, rows=None):
-    from harness import GpuRun
+    from harness import DevicePass
     print("case", wl.name, "seqlens", np.diff(wl.cu_seqlens).tolist(), "heads", wl.n_q_heads, wl.n_kv_heads,
           "block", wl.block, flush=True)
-    run = GpuRun(wl)
+    run = DevicePass(wl)
     run.mass_step()
     torch.cuda.synchronize()
     m_g = run.mass_host()
@@ -48,9 +48,9 @@ def test_block_mass_ragged_varlen_gqa(block):
 
 
 def test_block_mass_is_deterministic():
-    from harness import GpuRun
+    from harness import DevicePass
     wl = make_workload(1, seqlens=[3000])
-    run = GpuRun(wl)
+    run = DevicePass(wl)
     run.mass_step()
     torch.cuda.synchronize()
     a = run.mass_flat_host().copy()
@@ -63,7 +63,7 @@ def test_profile_feeds_budget_shifting_and_rates_the_selection():
     # The whole offline-to-online chain on a scaled-down benchmark layer: profile -> recovery curves ->
     # max-min shifted budgets -> pooled-score selection -> how much attention weight that selection keeps,
     # against the best any selection of the same size could keep (the curve itself).
-    from harness import GpuRun
+    from harness import DevicePass
     wl = make_workload(1, seqlens=[128 * 40])
     run, m_g, m_o = _profile(wl)
     curves = S.shplb_recovery_curves(run.p, run.mass_flat_host())
@@ -76,7 +76,7 @@ def test_profile_feeds_budget_shifting_and_rates_the_selection():
     shifted_min = min(curves[h, budgets[h]] for h in range(hq))
     assert shifted_min >= equal_min                       # what the shifting is for
     wl.budgets = budgets.astype(np.int32)
-    run2 = GpuRun(wl).run_all()
+    run2 = DevicePass(wl).run_all()
     kept = orc.selection_recovery(m_o, wl.cu_seqlens, wl.block, run2.sel_ptr_host, run2.sel_idx_host())
     best = np.array([curves[h, budgets[h]] for h in range(hq)])
     print("  budgets %s\n  kept by pooled-score selection %s\n  best possible %s" %

@@ -16,10 +16,10 @@ pytestmark = pytest.mark.gpu
 
 
 def _run(wl, budgets, softmax_scale=0.0):
-    from harness import GpuRun
+    from harness import DevicePass
     print("case", wl.name, "seqlens", np.diff(wl.cu_seqlens).tolist(), "heads", wl.n_q_heads, wl.n_kv_heads,
           "block", wl.block, "budgets", list(budgets), flush=True)
-    run = GpuRun(wl, softmax_scale=softmax_scale)
+    run = DevicePass(wl, softmax_scale=softmax_scale)
     run.token_recovery_step(budgets)
     torch.cuda.synchronize()
     return run, run.token_recovery.cpu().numpy()

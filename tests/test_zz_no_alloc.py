@@ -12,10 +12,10 @@ pytestmark = pytest.mark.gpu
 
 
 def _both_ways(wl):
-    from harness import GpuRun
+    from harness import DevicePass
     print("case", wl.name, "seqlens", np.diff(wl.cu_seqlens).tolist(), "heads", wl.n_q_heads, wl.n_kv_heads,
           "block", wl.block, flush=True)
-    run = GpuRun(wl).run_all()                     # scores, selection, attention through the workspace entry point
+    run = DevicePass(wl).run_all()                     # scores, selection, attention through the workspace entry point
     ref_out, ref_lse = run.out.clone(), run.lse.clone()
     ref_stats = run.stats_host().copy()
     run.out.zero_()
@@ -61,9 +61,9 @@ def test_static_scratch_entry_point_in_a_hip_graph():
     # What the entry point is for: captured into a HIP graph (after one call outside the capture, which
     # looks up the array's address) and replayed with eager work in between; every replay must
     # reproduce the workspace entry point's result bit for bit.
-    from harness import GpuRun
+    from harness import DevicePass
     wl = make_workload(1, seqlens=[128 * 29 + 17])
-    run = GpuRun(wl).run_all()
+    run = DevicePass(wl).run_all()
     ref_out, ref_lse = run.out.clone(), run.lse.clone()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
