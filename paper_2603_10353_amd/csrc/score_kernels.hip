@@ -154,6 +154,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const int g = kv_head_of(meta, h);
   const int i_first = ti + 32 * wave;               // this wave's rows
   const int i_last = min(ti + kScoreTile, nb) - 1;  // last row of the workgroup
+  if (tj > i_last) return;                          // chunk entirely right of a short sequence's last row (before any copy is issued)
   const int n_jt = (min(tj + chunk, i_last + 1) - tj + kScoreJ - 1) / kScoreJ;   // 32-row K tiles with some j <= i
   const int64_t k_plane = int64_t(meta.n_kv_heads) * total_blocks * kHeadDim;
   const char* k_rows = reinterpret_cast<const char*>(k_planes + (int64_t(g) * total_blocks + meta.blk_begin[s]) * kHeadDim);
