@@ -155,7 +155,9 @@ def main():
             out.append("  %-32s %.6g" % (c, sq[c]))
         out.append("  derived:")
         if "SQ_INSTS_MFMA" in sq and "SQ_INSTS_VALU" in sq:
-            out.append("    other VALU instructions per MFMA = %.2f" % (sq["SQ_INSTS_VALU"] / sq["SQ_INSTS_MFMA"]))
+            # SQ_INSTS_VALU counts the MFMAs too
+            out.append("    other VALU instructions per MFMA = (SQ_INSTS_VALU - SQ_INSTS_MFMA) / SQ_INSTS_MFMA = %.2f"
+                       % (sq["SQ_INSTS_VALU"] / sq["SQ_INSTS_MFMA"] - 1.0))
         if "SQ_VALU_MFMA_BUSY_CYCLES" in sq and "SQ_BUSY_CU_CYCLES" in sq:
             out.append("    matrix pipe busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES) = %.1f%% of the cycles "
                        "the compute units are busy" % (100 * sq["SQ_VALU_MFMA_BUSY_CYCLES"] / (4 * sq["SQ_BUSY_CU_CYCLES"])))
