@@ -67,6 +67,15 @@ def test_gqa_ragged_varlen(block):
     full_parity(wl)
 
 
+@pytest.mark.parametrize("heads", [(28, 4), (40, 8), (12, 2), (5, 5), (3, 1)])
+def test_group_sizes_of_the_evaluated_models(heads):
+    # GQA groups that are no powers of two (the Qwen2.5 models of Section 5.1 have 28/4, 40/8 and 64/8 heads),
+    # MHA with an odd head count, and one KV head for all
+    hq, hkv = heads
+    budgets = [2 + (5 * h) % 9 for h in range(hq)]
+    full_parity(make_custom([700, 130], hq, hkv, 128, budgets, seed=300 + hq, name="heads_%d_%d" % heads))
+
+
 def test_config1_shape_scaled_down():
     # Llama-3-8B-shaped GQA layer (32/8 heads, block 128) at 4K tokens + a ragged tail
     full_parity(make_workload(1, seqlens=[4096 + 77]))
