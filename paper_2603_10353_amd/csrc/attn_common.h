@@ -74,6 +74,10 @@ __device__ __forceinline__ void pair_values(float x, float& lower, float& upper)
   lower = a;
   upper = b;
 }
+// The raw exchange: afterwards the upper half of a holds what the lower half of b held and vice versa.
+__device__ __forceinline__ void swap_halves(uint32_t& a, uint32_t& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
 __device__ __forceinline__ float pair_max(float x) {
   float a, b;
   pair_values(x, a, b);
