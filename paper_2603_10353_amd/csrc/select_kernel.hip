@@ -15,6 +15,11 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 
 __device__ __forceinline__ int popc64(uint64_t m) { return __builtin_popcountll(m); }
 
+// base + the number of set bits of m below this lane's own (v_mbcnt_lo, v_mbcnt_hi).
+__device__ __forceinline__ int rank_in(uint64_t m, int base) {
+  return int(__builtin_amdgcn_mbcnt_hi(uint32_t(m >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(m), uint32_t(base))));
+}
+
 // Maximum over the 64 lanes, as a scalar.  Four data-parallel-primitive steps make every lane of a
 // row of 16 hold its row's maximum (exchange inside pairs, inside quads, mirror inside 8, mirror
 // inside 16), then one lane per row is read: no LDS round trips, unlike six shuffle steps.
@@ -45,14 +50,6 @@ __device__ __forceinline__ uint32_t wave_max(uint32_t x) {
 template <int SLOTS>
 __device__ __forceinline__ void select_row(const float* __restrict__ srow, int32_t* __restrict__ out, int i,
                                            int want, int lane) {
-  uint32_t key[SLOTS];
-#pragma unroll
-  for (int c = 0; c < SLOTS; ++c) {
-    const int j = c * 64 + lane;
-    key[c] = 0;                                 // 0 is below every real key (keys of finite floats are > 0)
-    if (j >= 1 && j < i) key[c] = order_key(srow[j]);
-  }
-
   if (want >= i - 1) {                          // budget covers every candidate
 #pragma unroll
     for (int c = 0; c < SLOTS; ++c) {
@@ -60,6 +57,19 @@ __device__ __forceinline__ void select_row(const float* __restrict__ srow, int32
       if (j >= 1 && j < i) out[j] = j;
     }
     return;
+  }
+
+  // All loads of the row are issued before the first is used (the index is clamped to the diagonal
+  // entry, which exists, instead of branching around the load: a branch per slot makes every load
+  // wait for the one before it, and a row of 1024 scores then costs sixteen memory round trips).
+  float raw[SLOTS];
+#pragma unroll
+  for (int c = 0; c < SLOTS; ++c) raw[c] = srow[min(c * 64 + lane, i)];
+  uint32_t key[SLOTS];
+#pragma unroll
+  for (int c = 0; c < SLOTS; ++c) {
+    const int j = c * 64 + lane;
+    key[c] = (j >= 1 && j < i) ? order_key(raw[c]) : 0u;   // 0 is below every real key (keys of finite floats are > 0)
   }
 
   // All candidates lie between the smallest and the largest key, so t shares their common
@@ -77,6 +87,11 @@ __device__ __forceinline__ void select_row(const float* __restrict__ srow, int32
   kmin = ~wave_max(~kmin);
   const uint32_t differ = kmax ^ kmin;
   uint32_t t = kmax;                            // all candidates equal: ties only
+  // Kept up to date during the search, so that no counting pass is needed after it:
+  // at_least = count(key >= t) (>= want), above = count(key >= the lowest rejected probe) (< want);
+  // after bit 0 the lowest rejected probe is t + 1, so above = count(key > t).
+  int at_least = i - 1, above = 0;
+  bool exact = false;                           // a probe split off exactly `want` keys: no ties to ration
   if (differ != 0) {
     const int top = 31 - __builtin_clz(differ);  // highest bit in which two candidates differ
     t = top == 31 ? 0u : kmax & ~((2u << top) - 1u);
@@ -86,40 +101,39 @@ __device__ __forceinline__ void select_row(const float* __restrict__ srow, int32
 #pragma unroll
       for (int c = 0; c < SLOTS; ++c) cnt += popc64(__ballot(key[c] >= probe));
       if (cnt == want) {
-        t = probe - 1;                          // keys > t are exactly the `want` keys >= probe
+        t = probe;                              // the keys >= probe are exactly the selection
+        exact = true;
         break;
       }
-      if (cnt > want) t = probe;
+      if (cnt > want) {
+        t = probe;
+        at_least = cnt;
+      } else {
+        above = cnt;
+      }
     }
   }
-  int above = 0;
-#pragma unroll
-  for (int c = 0; c < SLOTS; ++c) above += popc64(__ballot(key[c] > t));
-  const int ties_wanted = want - above;         // >= 1 by construction of t
 
-  const uint64_t below_me = (uint64_t(1) << lane) - 1;
   int written = 0, ties_seen = 0;
-  int at_least = 0;
-#pragma unroll
-  for (int c = 0; c < SLOTS; ++c) at_least += popc64(__ballot(key[c] >= t));
-  if (at_least == want) {                       // every key equal to t is wanted (the usual case: no surplus ties)
+  if (exact || at_least == want) {              // every key >= t is wanted (the usual case: no surplus ties)
 #pragma unroll
     for (int c = 0; c < SLOTS; ++c) {
       const bool take = key[c] >= t;
       const uint64_t take_mask = __ballot(take);
-      if (take) out[1 + written + popc64(take_mask & below_me)] = c * 64 + lane;
+      if (take) out[rank_in(take_mask, 1 + written)] = c * 64 + lane;
       written += popc64(take_mask);
     }
     return;
   }
+  const int ties_wanted = want - above;         // >= 1 by construction of t
 #pragma unroll
   for (int c = 0; c < SLOTS; ++c) {
     const bool is_tie = key[c] == t;
     const uint64_t tie_mask = __ballot(is_tie);
-    const int tie_rank = ties_seen + popc64(tie_mask & below_me);
+    const int tie_rank = rank_in(tie_mask, ties_seen);
     const bool take = key[c] > t || (is_tie && tie_rank < ties_wanted);
     const uint64_t take_mask = __ballot(take);
-    if (take) out[1 + written + popc64(take_mask & below_me)] = c * 64 + lane;
+    if (take) out[rank_in(take_mask, 1 + written)] = c * 64 + lane;
     written += popc64(take_mask);
     ties_seen += popc64(tie_mask);
   }
