@@ -159,6 +159,18 @@ __global__ __launch_bounds__(64 * kXcds) void queue_scan_kernel(
 __device__ __forceinline__ void write_items(ItemRec* __restrict__ dst, int row, int64_t sel_begin, int64_t n_sel,
                                             int pieces, uint32_t* __restrict__ split_done,
                                             SplitCounters* __restrict__ split_count, int slot_capacity) {
+  if (pieces <= 1) {                     // a whole row: no 64-bit divisions for piece boundaries
+    ItemRec rec;
+    rec.row = row;
+    rec.n_sel = int32_t(max(n_sel, int64_t(0)));
+    rec.sel_begin = sel_begin;
+    rec.slot = -1;
+    rec.pieces = pieces;
+    rec.first_slot = -1;
+    rec.split_index = -1;
+    dst[0] = rec;
+    return;
+  }
   int slot = -1, entry = -1;
   if (pieces > 1) {
     slot = int(atomicAdd(&split_count->n_slots, uint32_t(pieces)));
