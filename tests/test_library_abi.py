@@ -225,3 +225,40 @@ def test_token_recovery_host_side():
         with pytest.raises(S.ShplbError) as e:
             S.shplb_token_recovery(p, fake, fake, budgets, fake)
         assert e.value.status == status, budgets
+
+
+def test_header_is_plain_c_and_a_c_program_links(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99, and a C caller must link and run the host entry points
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                    os.path.join(inc, "shplb.h")], check=True)
+    src = tmp_path / "caller.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "shplb.h"
+int main(void) {
+  /* the worked instance of list scheduling on three machines */
+  const int64_t costs[7] = {5, 5, 4, 4, 3, 3, 3};
+  int32_t part_of[7];
+  int64_t loads[3];
+  if (shplb_balance_heads(costs, 7, 3, 0, part_of, loads) != SHPLB_OK) return 1;
+  if (loads[0] != 11 || loads[1] != 8 || loads[2] != 8) return 2;
+  int32_t cu[2] = {0, 1000};
+  shplb_problem p = {1, cu, 8, 2, 128, 128, 8 * 128, 128, 2 * 128, 128, 0.0f, 0};
+  int64_t rows = 0;
+  if (shplb_num_rows(&p, &rows) != SHPLB_OK || rows != 8 * 8) return 3;
+  printf("%s\n", shplb_strerror(SHPLB_E_BUDGET));
+  return 0;
+}
+''')
+    exe = tmp_path / "caller"
+    lib = S.lib_path()
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), lib,
+                    "-Wl,-rpath," + os.path.dirname(lib)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
+    assert out.stdout.strip() != ""
