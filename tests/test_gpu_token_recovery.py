@@ -91,3 +91,21 @@ def test_32k_layer_at_the_profiled_budget_on_sampled_queries():
     heads = S.shplb_token_recovery_heads(run.p, got)
     print("  recovery per head at k = 4096:", np.round(heads[:, 0], 3), flush=True)
     assert heads.min() > 0.125 and heads.max() <= 1 + 1e-5        # a head recovers at least k/T by taking any k keys
+
+
+def test_128k_layer_two_budgets_on_sampled_queries():
+    # the longest context of the evaluation: 1024 key blocks per row, two budgets in one call
+    wl = make_workload(2)
+    T = int(wl.cu_seqlens[-1])
+    budgets = [1024, 4096]
+    run, got = _run(wl, budgets)
+    assert not np.isnan(got).any() and (got > 0).all() and (got <= 1 + 1e-5).all()
+    np.testing.assert_array_equal(got[0][:, :1024], 1.0)
+    np.testing.assert_array_equal(got[1][:, :4096], 1.0)
+    worst = float((got[0] - got[1]).max())
+    print("  largest amount by which 1024 keys exceed 4096 keys: %.3g" % worst, flush=True)
+    assert worst <= 2e-5                                           # more keys never hold less (fp32 sums of 4096 terms)
+    rng = np.random.default_rng(13)
+    tokens = sorted({1023, 1024, 4096, T - 1} | set(rng.integers(4096, T, size=20).tolist()))
+    want = orc.token_recovery(wl.q, wl.k, wl.cu_seqlens, budgets, tokens=tokens)
+    np.testing.assert_allclose(got[:, :, tokens], want[:, :, tokens], rtol=TOKEN_RECOVERY_RTOL, atol=TOKEN_RECOVERY_ATOL)
