@@ -72,26 +72,55 @@ __device__ __forceinline__ void select_row(const float* __restrict__ srow, int32
     key[c] = (j >= 1 && j < i) ? order_key(raw[c]) : 0u;   // 0 is below every real key (keys of finite floats are > 0)
   }
 
-  // All candidates lie between the smallest and the largest key, so t shares their common
-  // leading bits (for scores of one sign and similar magnitude: sign and most of the
-  // exponent); the search starts below them.  It ends early when a probe splits off exactly
-  // `want` keys: those are the selection, whatever the lower bits of t would be.
+  // Scores of both signs are the rule, and the keys of the two signs lie far apart (the keys of small
+  // magnitudes of either sign are the ones near the middle of the range), so a search over both would
+  // spend its first steps on sign and exponent bits that split off nothing.  The want-th largest key is
+  // non-negative if at least `want` keys are, else negative: one count decides, and the search is
+  // confined to that sign.
+  constexpr uint32_t kSign = 0x80000000u;
+  int n_pos = 0;
+#pragma unroll
+  for (int c = 0; c < SLOTS; ++c) n_pos += popc64(__ballot(key[c] >= kSign));
+  const bool among_pos = want <= n_pos;
+  // All keys of that sign lie between its smallest and its largest, so t shares their common leading
+  // bits (for scores of similar magnitude: most of the exponent); the search starts below them.  It
+  // ends early when a probe splits off exactly `want` keys: those are the selection, whatever the
+  // lower bits of t would be.
   uint32_t kmax = 0, kmin = 0xffffffffu;
 #pragma unroll
-  for (int c = 0; c < SLOTS; ++c)
-    if (key[c] != 0) {
+  for (int c = 0; c < SLOTS; ++c) {
+    const bool in = among_pos ? key[c] >= kSign : key[c] - 1u < kSign - 1u;   // (the 0 of an empty slot is in neither)
+    if (in) {
       kmax = max(kmax, key[c]);
       kmin = min(kmin, key[c]);
     }
+  }
   kmax = wave_max(kmax);
   kmin = ~wave_max(~kmin);
-  const uint32_t differ = kmax ^ kmin;
-  uint32_t t = kmax;                            // all candidates equal: ties only
+  uint32_t differ = kmax ^ kmin;
+  uint32_t t = kmax;                            // all keys of the sign equal: ties only
   // Kept up to date during the search, so that no counting pass is needed after it:
   // at_least = count(key >= t) (>= want), above = count(key >= the lowest rejected probe) (< want);
-  // after bit 0 the lowest rejected probe is t + 1, so above = count(key > t).
-  int at_least = i - 1, above = 0;
+  // after bit 0 the lowest rejected probe is t + 1, so above = count(key > t).  Keys of the other sign
+  // are below every probe (negative ones) or above every probe (non-negative ones, counted from the start).
+  int at_least = among_pos ? n_pos : i - 1, above = among_pos ? 0 : n_pos;
   bool exact = false;                           // a probe split off exactly `want` keys: no ties to ration
+  if (n_pos == want) {                          // the non-negative keys are the selection
+    t = kSign;
+    exact = true;
+    differ = 0;
+  } else {
+    // Keys are taken relative to the smallest of their sign (keys below it, and the 0 of empty slots,
+    // become 0: a subtraction that saturates).  The order is the same, and the leading bits of the
+    // largest key now count the exponents the keys really span instead of all the bits from the first
+    // one in which two of them differ: about two steps fewer on pooled scores.
+    const uint32_t shift = kmin - 1u;
+#pragma unroll
+    for (int c = 0; c < SLOTS; ++c) key[c] = __builtin_elementwise_sub_sat(key[c], shift);
+    kmax -= shift;
+    differ = kmax ^ 1u;                         // the smallest key is now 1
+    t = kmax;
+  }
   if (differ != 0) {
     const int top = 31 - __builtin_clz(differ);  // highest bit in which two candidates differ
     t = top == 31 ? 0u : kmax & ~((2u << top) - 1u);
