@@ -117,7 +117,7 @@ def cpu_baseline(wl, sel_ptr, sel_idx, budget_s=15.0):
         nq = o.shape[0]
         pairs += (len(sel) - 1) * nq * blk + nq * (nq + 1) // 2
         rows.append(r)
-        if t_used >= budget_s or len(rows) >= 512:
+        if t_used >= budget_s or len(rows) >= 1024:
             break
     rec = dict(value=4.0 * d * pairs / t_used / 1e12, unit="TFLOP/s", cores=int(cores), kind="oracle",
                sample="attention oracle (numpy fp64) on %d seeded (head, query-block) rows incl. the 4 "
