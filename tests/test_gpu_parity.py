@@ -300,6 +300,36 @@ def test_select_kernel_bit_exact_on_given_scores():
     np.testing.assert_array_equal(run.sel_idx_host(), idx_o)
 
 
+def test_select_kernel_on_scores_of_one_sign_and_of_extreme_range():
+    # The search runs inside the sign that holds the threshold, on keys relative to that sign's smallest:
+    # rows of one sign only, rows with exactly the wanted number of non-negative scores, magnitudes from
+    # denormals to 1e30, and distinct values throughout (no ties to hide behind).
+    nb = 300
+    budgets = [2, 3, 12, 40, 130, 299, 7, 77]
+    wl = make_custom([64 * nb], 8, 8, 64, budgets, seed=52, name="signs")
+    run = _gpu()(wl)
+    rng = np.random.default_rng(6)
+    sc = np.zeros((8, nb, nb), np.float32)
+    mag = lambda shape: np.exp(rng.uniform(np.log(1e-30), np.log(1e30), size=shape)).astype(np.float32)
+    sc[0] = -mag((nb, nb))                                   # all negative
+    sc[1] = mag((nb, nb))                                    # all positive
+    sc[2] = rng.standard_normal((nb, nb)).astype(np.float32) * 1e-40   # denormals of both signs
+    sc[3] = rng.standard_normal((nb, nb)).astype(np.float32)
+    for h in (4, 5, 6, 7):                                   # exactly want = k - 2 non-negative candidates per row
+        want = budgets[h] - 2
+        base = -mag((nb, nb))
+        for i in range(nb):
+            cand = np.arange(1, i)
+            if 0 < want < len(cand):
+                base[i, rng.choice(cand, size=want, replace=False)] *= -1.0
+        sc[h] = base
+    run.select_step(torch.from_numpy(sc.reshape(-1)).to("cuda:0"))
+    torch.cuda.synchronize()
+    ptr_o, idx_o = orc.select_blocks([sc], wl.budgets)
+    np.testing.assert_array_equal(run.sel_ptr_host, ptr_o)
+    np.testing.assert_array_equal(run.sel_idx_host(), idx_o)
+
+
 def test_deterministic_across_runs():
     wl = make_workload(1, seqlens=[2048])
     run = _gpu()(wl).run_all()
