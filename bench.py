@@ -125,6 +125,42 @@ def cpu_baseline(wl, sel_ptr, sel_idx, budget_s=15.0):
     return rec, outs
 
 
+class ClockSampler:
+    """Shader clock as the driver reports it (rocm-smi), sampled from a thread while the device works."""
+
+    def __init__(self):
+        import threading
+        self.samples, self.stop = [], False
+        self.thread = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import re
+        import subprocess
+        while not self.stop:
+            t = time.perf_counter()
+            try:
+                out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True,
+                                     timeout=10).stdout
+                m = re.search(r"sclk clock speed:\W+(\d+)Mhz", out)
+                if m:
+                    self.samples.append((t, int(m.group(1))))
+            except Exception:
+                return
+            time.sleep(0.02)
+
+    def __enter__(self):
+        self.thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self.stop = True
+        self.thread.join(timeout=15)
+
+    def median_mhz(self, t0, t1):
+        got = sorted(v for (t, v) in self.samples if t0 <= t <= t1)
+        return (got[len(got) // 2], len(got)) if got else (None, 0)
+
+
 class Pass:
     """Device-resident buffers of one workload and the timed loop over whole steps."""
 
@@ -233,6 +269,9 @@ def main():
     ap.add_argument("--split-slots", type=int, default=0,
                     help="run the attention step through shplb_sparse_attn_prefill_split with this many "
                          "partial-result slots (long rows cut along the keys); 0 = whole rows")
+    ap.add_argument("--sample-clocks", action="store_true",
+                    help="sample the shader clock (rocm-smi) from a thread during the timed steps and report its "
+                         "median as sclk_during_timed_steps; use with enough --steps to last a few seconds")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -274,7 +313,16 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    m = run.measure(args.steps, args.warmup)
+    if args.sample_clocks:
+        with ClockSampler() as clocks:
+            t0 = time.perf_counter()
+            m = run.measure(args.steps, args.warmup)
+            t1 = time.perf_counter()
+        # samples from the timed steps only (the warm-up comes first; leave it a margin)
+        mhz, n = clocks.median_mhz(t1 - 0.9 * args.steps * m["ms_per_step"] * 1e-3, t1)
+        m["sclk"] = {"median_mhz": mhz, "samples": n, "source": "rocm-smi --showclocks during the timed steps"}
+    else:
+        m = run.measure(args.steps, args.warmup)
     attn_tflops = m["roofline"]["achieved"]
 
     result = {
@@ -294,6 +342,8 @@ def main():
         "roofline": m["roofline"],
         "host_input_generation_s": t_gen,
     }
+    if "sclk" in m:
+        result["sclk_during_timed_steps"] = m["sclk"]
 
     if cfg == 2 and not args.no_32k:
         # The metric names two context lengths.  The 32K layer (workload cfg1) is measured the same
